@@ -1,0 +1,188 @@
+/*
+ * marl_decode.h — C ABI of the MI355X (gfx950) rollout-decode library.
+ *
+ * The library computes the two data-parallel operations that one decode step of multi-agent
+ * RL rollout spends its time in: single-token attention over a paged KV cache whose prompts
+ * are each expanded into several samples sharing the prompt's prefix, and the per-token
+ * log-probability that RL training consumes.  The paper motivates both (rollout is
+ * memory-bound on KV caches: Section 4.1; several samples per prompt: Section 5.1 and the
+ * parallelism settings of Section 8.1; skewed agent load: Section 2.2, Observation #2; GRPO
+ * training: Section 8.1) but delegates them to a black-box inference backend (Section 7), so
+ * the operations are the textbook ones, stated with every entry point below.
+ *
+ * Conventions for every entry point
+ *   - Pointers named "device" are GPU addresses owned by the caller; the library never
+ *     allocates, frees or keeps them.  `stream` is a hipStream_t (NULL = default stream).
+ *   - Calls only enqueue work on `stream` and return; nothing synchronises with the host.
+ *   - Return value: MARL_OK (0) or a negative marl_status.  Arguments are validated on the
+ *     host before any HIP call, so argument errors are reported without touching the GPU.
+ *     Contents of device arrays cannot be validated without a sync; instead the kernels
+ *     clamp what they read (lengths to the table extents, page ids to [0, num_pages),
+ *     group ids outside [0, num_groups) mean "no prefix") so bad contents never cause an
+ *     out-of-range access, and record a flag readable with marl_attn_read_flags().
+ *   - bf16 means the upper 16 bits of an IEEE float32; conversions round to nearest even.
+ */
+#ifndef MARL_DECODE_H
+#define MARL_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum marl_status {
+  MARL_OK = 0,
+  MARL_INVALID_ARG = -1,   /* null pointer, negative count, Hq % Hkv != 0, non-finite scalar */
+  MARL_UNSUPPORTED = -2,   /* head_dim != 128, page_size != 16, unknown out_dtype, bad chunk */
+  MARL_WORKSPACE_TOO_SMALL = -3,
+  MARL_HIP_ERROR = -4      /* a launch failed; marl_last_hip_error() has the text */
+} marl_status;
+
+enum { MARL_OUT_BF16 = 0, MARL_OUT_F32 = 1 };
+
+/* Shape of one marl_decode_attn call (host memory). */
+typedef struct marl_attn_shape {
+  int32_t num_seqs;          /* NS >= 0 */
+  int32_t num_groups;        /* NG >= 0: shared-prefix groups (prompts) */
+  int32_t num_q_heads;       /* Hq */
+  int32_t num_kv_heads;      /* Hkv, Hq % Hkv == 0, Hq / Hkv <= 16 */
+  int32_t head_dim;          /* must be 128 */
+  int32_t page_size;         /* must be 16 */
+  int32_t num_pages;         /* extent of k_pages / v_pages along dim 0, >= 1 */
+  int32_t max_prefix_pages;  /* row stride of prefix_block_table, >= 0 */
+  int32_t max_suffix_pages;  /* row stride of suffix_block_table, >= 0 */
+  int32_t out_dtype;         /* MARL_OUT_BF16 or MARL_OUT_F32 */
+  int32_t suffix_chunk_tokens; /* 0 = library default; else a multiple of 32 in [32, 65536] */
+  int32_t prefix_chunk_tokens; /* 0 = library default; else a multiple of 32 in [32, 65536] */
+} marl_attn_shape;
+
+/* How the library lays out its workspace for a shape (host-only; for sizing and for tests
+ * that read the work list back).  All offsets are in bytes from the workspace start. */
+typedef struct marl_attn_plan_layout {
+  int32_t suffix_chunk_tokens;   /* Cs actually used */
+  int32_t prefix_chunk_tokens;   /* Cp actually used */
+  int32_t suffix_slots;          /* NCs = max(1, ceil(max_suffix_pages*16 / Cs)) */
+  int32_t prefix_slots;          /* NCp = max(1, ceil(max_prefix_pages*16 / Cp)) */
+  int32_t rows_per_qblock;       /* query rows one prefix work item covers (64) */
+  int32_t max_suffix_items;      /* NS * NCs */
+  int32_t max_prefix_items;      /* (NG + NS*(Hq/Hkv)/rows_per_qblock + 1) * NCp */
+  int32_t reserved;
+  size_t counters_off;           /* int32[64]: see MARL_CTR_* */
+  size_t group_count_off;        /* int32[NG]   sequences per group */
+  size_t group_start_off;        /* int32[NG+1] exclusive scan of group_count */
+  size_t seq_rank_off;           /* int32[NS]   scratch */
+  size_t group_seqs_off;         /* int32[NS]   sequence ids grouped by group (CSR values) */
+  size_t suffix_items_off;       /* int32[max_suffix_items][4] {seq, tok_begin, tok_end, 0} */
+  size_t prefix_items_off;       /* int32[max_prefix_items][4] {group, tok_begin, tok_end, row_begin} */
+  size_t partial_ml_off;         /* float[NS][Hq][NCp+NCs][2]  (max, sum) per partial */
+  size_t partial_o_off;          /* float[NS][Hq][NCp+NCs][128] unnormalised partial output */
+  size_t total_bytes;
+} marl_attn_plan_layout;
+
+enum {
+  MARL_CTR_NUM_SUFFIX_ITEMS = 0,
+  MARL_CTR_NUM_PREFIX_ITEMS = 1,
+  MARL_CTR_SUFFIX_CURSOR = 2,    /* work-queue cursors, zero after the plan kernel */
+  MARL_CTR_PREFIX_CURSOR = 3,
+  MARL_CTR_FLAGS = 4             /* MARL_FLAG_* bits set by the kernels */
+};
+enum {
+  MARL_FLAG_BAD_GROUP = 1,       /* a group_of_seq entry was outside [0, NG) */
+  MARL_FLAG_LEN_CLAMPED = 2,     /* a length was negative or exceeded its table row */
+  MARL_FLAG_BAD_PAGE = 4         /* a block-table entry of a valid token was outside [0, num_pages) */
+};
+
+/* Fills *layout for *shape.  Host-only, no GPU needed.
+ * Chunking rule when the shape gives 0:  Cs starts at 2048 and is halved while
+ * NS*Hkv*ceil(max_suffix_tokens/Cs) < 2048 and Cs > 256;  Cp starts at 1024 and is halved
+ * while NG*Hkv*ceil(max_prefix_tokens/Cp) < 1024 and Cp > 256. */
+int marl_attn_plan_layout_for(const marl_attn_shape* shape, marl_attn_plan_layout* layout);
+
+/* *bytes = layout.total_bytes (an upper bound that depends on the shape only). Host-only. */
+int marl_workspace_bytes(const marl_attn_shape* shape, size_t* bytes);
+
+/*
+ * Batched single-token attention over a paged KV cache with shared prefixes.
+ *
+ * For sequence s with group g = group_of_seq[s] and query head h (KV head kh = h / (Hq/Hkv)),
+ * the logical tokens are the P = prefix_lens[g] prefix tokens of the group followed by the
+ * S = suffix_lens[s] tokens the sequence generated itself (the current token included: the
+ * call only reads the cache).  Prefix token j is at page prefix_block_table[g][j/16], slot
+ * j%16; suffix token j' at page suffix_block_table[s][j'/16], slot j'%16.  With
+ * x_j = scale * <q[s,h,:], K_j>, the result is out[s,h,:] = sum_j softmax(x)_j V_j, and zeros
+ * when P + S == 0.
+ *
+ * Device arrays:
+ *   q                   bf16  [NS, Hq, 128]
+ *   k_pages             bf16  [num_pages, Hkv, 16 slots, 128]   (a token's key is contiguous)
+ *   v_pages             bf16  [num_pages, Hkv, 128, 16 slots]   (a channel's 16 slots are contiguous)
+ *   prefix_block_table  int32 [NG, max_prefix_pages]   entries past a row's pages are ignored (-1 by convention)
+ *   suffix_block_table  int32 [NS, max_suffix_pages]
+ *   prefix_lens         int32 [NG]  tokens
+ *   suffix_lens         int32 [NS]  tokens
+ *   group_of_seq        int32 [NS]  in [0, NG); a group's sequences may appear in any order
+ *   out                 bf16 or float32 [NS, Hq, 128] per shape->out_dtype
+ *   workspace           at least marl_workspace_bytes() bytes, 256-byte aligned; contents on
+ *                       entry are irrelevant, contents on exit are the work list and partials
+ * Unused slots of a partly filled page and pages no table names are never read into a result.
+ * Calls that share a workspace must be ordered on one stream.
+ *
+ * Work: a plan kernel builds the group->sequences CSR and two work lists (prefix items per
+ * group, suffix items per sequence, each at most a chunk of tokens, longest first); a
+ * prefix kernel streams each group's prefix KV once for all of the group's query rows; a
+ * suffix kernel streams each sequence's own KV; a merge kernel combines the per-chunk
+ * (max, sum, output) partials in a fixed order, so results are bit-identical across runs.
+ */
+int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t workspace_bytes,
+                     const void* q, const void* k_pages, const void* v_pages,
+                     const int32_t* prefix_block_table, const int32_t* suffix_block_table,
+                     const int32_t* prefix_lens, const int32_t* suffix_lens,
+                     const int32_t* group_of_seq, float scale, void* out, void* stream);
+
+/* Runs only the plan kernel of marl_decode_attn (same arguments' meaning); after it, the
+ * workspace holds the CSR, the work lists and the counters described by the layout. */
+int marl_attn_plan(const marl_attn_shape* shape, void* workspace, size_t workspace_bytes,
+                   const int32_t* prefix_lens, const int32_t* suffix_lens,
+                   const int32_t* group_of_seq, void* stream);
+
+/* Copies the MARL_FLAG_* word of a workspace to *flags_host.  Synchronises `stream`. */
+int marl_attn_read_flags(const void* workspace, int32_t* flags_host, void* stream);
+
+/*
+ * Per-row log-probability of one chosen token:
+ *   out[r] = logits[r, tokens[r]] / T - log( sum_v exp(logits[r, v] / T) )
+ * Device arrays: logits bf16 [rows, vocab] (row stride = vocab elements), tokens int32
+ * [rows], out float32 [rows].  A token id outside [0, vocab) gives NaN for that row.
+ * temperature must be finite and > 0.  workspace: marl_logprobs_workspace_bytes() bytes
+ * (may be 0, then workspace may be NULL), 256-byte aligned.
+ */
+int marl_logprobs_workspace_bytes(int32_t rows, int32_t vocab, size_t* bytes);
+int marl_token_logprobs(const void* logits, const int32_t* tokens, float temperature, float* out,
+                        int32_t rows, int32_t vocab, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/*
+ * Per-kernel timing of marl_decode_attn / marl_token_logprobs calls (for benchmarks).
+ * After marl_profile_begin(max_calls) every call records HIP events around each of its
+ * kernels on the call's stream (no synchronisation).  marl_profile_end() synchronises the
+ * device, writes the average duration in milliseconds of each stage over the recorded
+ * calls (MARL_STAGE_* indices; stages that never ran stay 0), the number of recorded
+ * attention calls and log-prob calls, and switches recording off.
+ */
+enum {
+  MARL_STAGE_PLAN = 0, MARL_STAGE_PREFIX = 1, MARL_STAGE_SUFFIX = 2, MARL_STAGE_MERGE = 3,
+  MARL_STAGE_LOGPROB = 4, MARL_STAGE_LOGPROB_FINISH = 5, MARL_NUM_STAGES = 6
+};
+int marl_profile_begin(int32_t max_calls);
+int marl_profile_end(float stage_ms[MARL_NUM_STAGES], int32_t* attn_calls, int32_t* logprob_calls);
+
+const char* marl_status_string(int status);
+const char* marl_last_hip_error(void);
+int marl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MARL_DECODE_H */

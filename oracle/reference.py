@@ -1,0 +1,159 @@
+"""Python face of the reference checker (TEST INFRASTRUCTURE ONLY).
+
+Loads the float64 C loops of `marl_oracle.c` and adds the few pieces that are easier to
+state in numpy: the (max, sum, weighted-values) summary of a slice of tokens and the rule
+that combines such summaries (the algebra any split-KV scheme relies on).  Only tests, the
+smoke check and the CPU-baseline leg of the benchmark import this; it shares nothing with
+the GPU library and never imports it.
+
+Definitions are the textbook ones (the paper, Sections 4.1, 5.1 and 7, motivates the decode
+step but prints no formula for it); see the header of `marl_oracle.c`.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "marl_oracle.c")
+_LIB = os.path.join(_HERE, "libmarl_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C checker with gcc (no GPU toolchain involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        P = ctypes.c_void_p
+        I = ctypes.c_int
+        lib.oracle_decode_attn.restype = I
+        lib.oracle_decode_attn.argtypes = [I, I, I, I, P, P, P, P, I, P, I, P, P, P,
+                                           ctypes.c_double, P, I, I, I]
+        lib.oracle_attn_weights.restype = I
+        lib.oracle_attn_weights.argtypes = [I, I, I, I, P, P, P, P, I, P, I, P, P, P,
+                                            ctypes.c_double, P, P]
+        lib.oracle_token_logprobs.restype = I
+        lib.oracle_token_logprobs.argtypes = [I, I, P, P, ctypes.c_double, P, I]
+        _lib = lib
+    return _lib
+
+
+def _u16(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def decode_attn(q, k_pages, v_pages, prefix_table, suffix_table, prefix_lens, suffix_lens,
+                group_of_seq, scale: float, Hq: int, Hkv: int,
+                seq_range: Optional[Tuple[int, int]] = None, threads: int = 0,
+                return_threads: bool = False):
+    """q, k_pages, v_pages: uint16 arrays of bf16 bit patterns in the ABI layout.
+    Returns float64 [NS, Hq, 128] (rows outside `seq_range` stay zero)."""
+    lib = _load()
+    q, k_pages, v_pages = _u16(q), _u16(k_pages), _u16(v_pages)
+    pt, st = _i32(prefix_table), _i32(suffix_table)
+    pl, sl, gos = _i32(prefix_lens), _i32(suffix_lens), _i32(group_of_seq)
+    NS, NG = sl.shape[0], pl.shape[0]
+    pt = pt.reshape(NG, -1) if pt.size else pt.reshape(NG, 0)
+    st = st.reshape(NS, -1) if st.size else st.reshape(NS, 0)
+    out = np.zeros((NS, Hq, 128), dtype=np.float64)
+    b, e = (0, NS) if seq_range is None else seq_range
+    used = lib.oracle_decode_attn(NS, NG, Hq, Hkv, _ptr(q), _ptr(k_pages), _ptr(v_pages),
+                                  _ptr(pt), pt.shape[1], _ptr(st), st.shape[1], _ptr(pl), _ptr(sl),
+                                  _ptr(gos), float(scale), _ptr(out), b, e, threads)
+    if used < 0:
+        raise MemoryError("oracle_decode_attn")
+    return (out, used) if return_threads else out
+
+
+def attn_weights(s: int, h: int, q, k_pages, v_pages, prefix_table, suffix_table, prefix_lens,
+                 suffix_lens, group_of_seq, scale: float, Hq: int, Hkv: int):
+    """Softmax weights over the logical tokens of one (sequence, head), and its output row."""
+    lib = _load()
+    q, k_pages, v_pages = _u16(q), _u16(k_pages), _u16(v_pages)
+    pt, st = _i32(prefix_table), _i32(suffix_table)
+    pl, sl, gos = _i32(prefix_lens), _i32(suffix_lens), _i32(group_of_seq)
+    NS, NG = sl.shape[0], pl.shape[0]
+    pt, st = pt.reshape(NG, -1), st.reshape(NS, -1)
+    L = int(pl[gos[s]]) + int(sl[s])
+    w = np.zeros(max(L, 1), dtype=np.float64)
+    out = np.zeros(128, dtype=np.float64)
+    lib.oracle_attn_weights(s, h, Hq, Hkv, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(pt),
+                            pt.shape[1], _ptr(st), st.shape[1], _ptr(pl), _ptr(sl), _ptr(gos),
+                            float(scale), _ptr(out), _ptr(w))
+    return w[:L], out
+
+
+def token_logprobs(logits, tokens, temperature: float, threads: int = 0,
+                   return_threads: bool = False):
+    """logits: uint16 bf16 bit patterns [rows, vocab].  Returns float64 [rows]."""
+    lib = _load()
+    logits = _u16(logits)
+    rows, vocab = logits.shape
+    tok = _i32(tokens)
+    out = np.zeros(rows, dtype=np.float64)
+    used = lib.oracle_token_logprobs(rows, vocab, _ptr(logits), _ptr(tok), float(temperature),
+                                     _ptr(out), threads)
+    return (out, used) if return_threads else out
+
+
+# ------------------------------------------------------------------------------------------
+# The summary of a slice of tokens and the rule that merges summaries.  For scores x_j and
+# value rows v_j of a slice:  m = max_j x_j,  l = sum_j exp(x_j - m),  O = sum_j exp(x_j - m) v_j.
+# Two slices combine as  m* = max(m1, m2),  l* = l1 e^{m1-m*} + l2 e^{m2-m*},
+# O* = O1 e^{m1-m*} + O2 e^{m2-m*};  the attention output of the union is O*/l*.
+# ------------------------------------------------------------------------------------------
+def slice_summary(scores: np.ndarray, values: np.ndarray):
+    """scores float64 [n], values float64 [n, d] -> (m, l, O[d]); an empty slice gives
+    (-inf, 0, 0)."""
+    if scores.shape[0] == 0:
+        return -np.inf, 0.0, np.zeros(values.shape[1])
+    m = float(scores.max())
+    w = np.exp(scores - m)
+    return m, float(w.sum()), w @ values
+
+
+def merge_summaries(parts):
+    """Combine [(m, l, O), ...] in list order; returns the normalised output O*/l* (zeros if
+    every slice is empty)."""
+    ms = [p[0] for p in parts]
+    mstar = max(ms) if ms else -np.inf
+    if not np.isfinite(mstar):
+        d = parts[0][2].shape[0] if parts else 128
+        return np.zeros(d)
+    l = 0.0
+    O = np.zeros_like(parts[0][2])
+    for (m, li, Oi) in parts:
+        if li == 0.0:
+            continue
+        f = np.exp(m - mstar)
+        l += li * f
+        O = O + Oi * f
+    return O / l
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

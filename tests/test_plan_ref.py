@@ -1,0 +1,48 @@
+"""The host reference of the work list: coverage and ordering properties (CPU only)."""
+import numpy as np
+
+from oracle import plan_ref
+
+
+def test_every_token_is_covered_exactly_once():
+    rng = np.random.default_rng(0)
+    NG, G, Hq, Hkv = 5, 3, 8, 2
+    pl = rng.integers(0, 700, NG); sl = rng.integers(0, 900, NG * G); sl[2] = 0; pl[1] = 0
+    gos = rng.permutation(np.repeat(np.arange(NG), G))
+    mpp, msp = 44, 57
+    p = plan_ref.build_plan(pl, sl, gos, Hq, Hkv, mpp, msp, suffix_chunk=128, prefix_chunk=96)
+    assert p.flags == 0
+    for s in range(NG * G):
+        spans = sorted((a, b) for (i, a, b, _) in p.suffix_items if i == s)
+        assert [a for a, _ in spans] == list(range(0, int(sl[s]), 128))
+        assert sum(b - a for a, b in spans) == sl[s]
+        assert all(0 < b - a <= 128 for a, b in spans)
+    R = Hq // Hkv
+    for g in range(NG):
+        rows = int(p.group_count[g]) * R
+        items = [(a, b, r) for (i, a, b, r) in p.prefix_items if i == g]
+        cover = np.zeros((max(rows, 1), max(int(pl[g]), 1)), int)
+        for a, b, r in items:
+            cover[r:min(rows, r + plan_ref.ROWS_PER_QBLOCK), a:b] += 1
+        if rows and pl[g]:
+            assert (cover == 1).all()
+        else:
+            assert not items
+    for g in range(NG):
+        seg = p.group_seqs[p.group_start[g]:p.group_start[g + 1]]
+        assert list(seg) == sorted(np.nonzero(gos == g)[0])
+
+
+def test_clamping_and_bad_group_flags():
+    p = plan_ref.build_plan([40, -3], [10, 9999, 5], [0, 7, 1], 4, 2, 2, 3, 32, 32)
+    assert p.flags == 3
+    assert sorted(p.suffix_items) == [(0, 0, 10, 0), (1, 0, 32, 0), (1, 32, 48, 0), (2, 0, 5, 0)]
+    assert sorted(p.prefix_items) == [(0, 0, 32, 0)]
+    assert list(p.group_count) == [1, 1]
+
+
+def test_default_chunk_rule():
+    assert plan_ref.default_chunks(2048, 256, 4, 128, 512) == (2048, 1024)
+    assert plan_ref.default_chunks(16, 4, 2, 16, 8) == (256, 256)
+    assert plan_ref.default_chunks(256, 64, 8, 512, 1536) == (2048, 1024)
+    assert plan_ref.default_chunks(16, 4, 2, 16, 8, 64, 96) == (64, 96)
