@@ -1,0 +1,214 @@
+"""Thin ctypes binding of libmarl_decode.so (include/marl_decode.h): argument marshalling
+only.  PyTorch supplies device memory and the stream; every step runs in the library's
+kernels.  There is no fallback: if the library is missing or a call fails, this raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+from .build import LIB_PATH, build_library
+
+I32 = ctypes.c_int32
+SZ = ctypes.c_size_t
+VP = ctypes.c_void_p
+
+MARL_OUT_BF16, MARL_OUT_F32 = 0, 1
+STAGES = ("plan", "prefix", "suffix", "merge", "logprob", "logprob_finish")
+CTR_NUM_SUFFIX_ITEMS, CTR_NUM_PREFIX_ITEMS, CTR_SUFFIX_CURSOR, CTR_PREFIX_CURSOR, CTR_FLAGS = range(5)
+FLAG_BAD_GROUP, FLAG_LEN_CLAMPED, FLAG_BAD_PAGE = 1, 2, 4
+
+
+class AttnShape(ctypes.Structure):
+    _fields_ = [(n, I32) for n in (
+        "num_seqs", "num_groups", "num_q_heads", "num_kv_heads", "head_dim", "page_size",
+        "num_pages", "max_prefix_pages", "max_suffix_pages", "out_dtype",
+        "suffix_chunk_tokens", "prefix_chunk_tokens")]
+
+
+class PlanLayout(ctypes.Structure):
+    _fields_ = [(n, I32) for n in (
+        "suffix_chunk_tokens", "prefix_chunk_tokens", "suffix_slots", "prefix_slots",
+        "rows_per_qblock", "max_suffix_items", "max_prefix_items", "reserved")] + \
+        [(n, SZ) for n in (
+            "counters_off", "group_count_off", "group_start_off", "seq_rank_off", "group_seqs_off",
+            "suffix_items_off", "prefix_items_off", "partial_ml_off", "partial_o_off", "total_bytes")]
+
+
+class MarlError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({detail})")
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True):
+    """Loads the in-tree shared library; builds it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    PS, PL = ctypes.POINTER(AttnShape), ctypes.POINTER(PlanLayout)
+    lib.marl_version.restype = ctypes.c_int
+    lib.marl_status_string.restype = ctypes.c_char_p
+    lib.marl_status_string.argtypes = [ctypes.c_int]
+    lib.marl_last_hip_error.restype = ctypes.c_char_p
+    lib.marl_attn_plan_layout_for.argtypes = [PS, PL]
+    lib.marl_workspace_bytes.argtypes = [PS, ctypes.POINTER(SZ)]
+    lib.marl_decode_attn.argtypes = [PS, VP, SZ, VP, VP, VP, VP, VP, VP, VP, VP, ctypes.c_float, VP, VP]
+    lib.marl_attn_plan.argtypes = [PS, VP, SZ, VP, VP, VP, VP]
+    lib.marl_attn_read_flags.argtypes = [VP, ctypes.POINTER(I32), VP]
+    lib.marl_logprobs_workspace_bytes.argtypes = [I32, I32, ctypes.POINTER(SZ)]
+    lib.marl_token_logprobs.argtypes = [VP, VP, ctypes.c_float, VP, I32, I32, VP, SZ, VP]
+    lib.marl_profile_begin.argtypes = [I32]
+    lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
+    for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_attn_plan",
+              "marl_attn_read_flags", "marl_logprobs_workspace_bytes", "marl_token_logprobs",
+              "marl_profile_begin", "marl_profile_end"):
+        getattr(lib, f).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        lib = load_library()
+        detail = lib.marl_status_string(rc).decode()
+        if rc == -4:
+            detail += ": " + lib.marl_last_hip_error().decode()
+        raise MarlError(rc, where, detail)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def make_shape(num_seqs, num_groups, num_q_heads, num_kv_heads, num_pages, max_prefix_pages,
+               max_suffix_pages, out_dtype=MARL_OUT_BF16, suffix_chunk_tokens=0, prefix_chunk_tokens=0,
+               head_dim=128, page_size=16) -> AttnShape:
+    return AttnShape(num_seqs, num_groups, num_q_heads, num_kv_heads, head_dim, page_size, num_pages,
+                     max_prefix_pages, max_suffix_pages, out_dtype, suffix_chunk_tokens, prefix_chunk_tokens)
+
+
+def marl_attn_plan_layout_for(shape: AttnShape) -> PlanLayout:
+    L = PlanLayout()
+    _check(load_library().marl_attn_plan_layout_for(ctypes.byref(shape), ctypes.byref(L)), "marl_attn_plan_layout_for")
+    return L
+
+
+def marl_workspace_bytes(shape: AttnShape) -> int:
+    n = SZ(0)
+    _check(load_library().marl_workspace_bytes(ctypes.byref(shape), ctypes.byref(n)), "marl_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_workspace(nbytes: int, device) -> torch.Tensor:
+    """Device bytes, 256-byte aligned (torch's allocator aligns to 512)."""
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _require_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("device tensors required: the library has no CPU path")
+        if t is not None and not t.is_contiguous():
+            raise ValueError("contiguous tensors required")
+
+
+def marl_decode_attn(shape: AttnShape, workspace: torch.Tensor, q, k_pages, v_pages, prefix_block_table,
+                     suffix_block_table, prefix_lens, suffix_lens, group_of_seq, scale: float,
+                     out: torch.Tensor) -> torch.Tensor:
+    _require_cuda(workspace, q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens,
+                  suffix_lens, group_of_seq, out)
+    rc = load_library().marl_decode_attn(
+        ctypes.byref(shape), _ptr(workspace), workspace.numel(), _ptr(q), _ptr(k_pages), _ptr(v_pages),
+        _ptr(prefix_block_table), _ptr(suffix_block_table), _ptr(prefix_lens), _ptr(suffix_lens),
+        _ptr(group_of_seq), float(scale), _ptr(out), _stream(out.device))
+    _check(rc, "marl_decode_attn")
+    return out
+
+
+def marl_attn_plan(shape: AttnShape, workspace: torch.Tensor, prefix_lens, suffix_lens, group_of_seq):
+    _require_cuda(workspace, prefix_lens, suffix_lens, group_of_seq)
+    rc = load_library().marl_attn_plan(ctypes.byref(shape), _ptr(workspace), workspace.numel(),
+                                       _ptr(prefix_lens), _ptr(suffix_lens), _ptr(group_of_seq),
+                                       _stream(workspace.device))
+    _check(rc, "marl_attn_plan")
+
+
+def marl_attn_read_flags(workspace: torch.Tensor) -> int:
+    _require_cuda(workspace)
+    f = I32(0)
+    _check(load_library().marl_attn_read_flags(_ptr(workspace), ctypes.byref(f), _stream(workspace.device)),
+           "marl_attn_read_flags")
+    return int(f.value)
+
+
+def marl_logprobs_workspace_bytes(rows: int, vocab: int) -> int:
+    n = SZ(0)
+    _check(load_library().marl_logprobs_workspace_bytes(rows, vocab, ctypes.byref(n)), "marl_logprobs_workspace_bytes")
+    return int(n.value)
+
+
+def marl_token_logprobs(logits: torch.Tensor, tokens: torch.Tensor, temperature: float, out: torch.Tensor,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _require_cuda(logits, tokens, out, workspace)
+    rows, vocab = logits.shape
+    rc = load_library().marl_token_logprobs(
+        _ptr(logits), _ptr(tokens), float(temperature), _ptr(out), rows, vocab, _ptr(workspace),
+        0 if workspace is None else workspace.numel(), _stream(logits.device))
+    _check(rc, "marl_token_logprobs")
+    return out
+
+
+def marl_profile_begin(max_calls: int):
+    _check(load_library().marl_profile_begin(max_calls), "marl_profile_begin")
+
+
+def marl_profile_end():
+    ms = (ctypes.c_float * len(STAGES))()
+    na, nl = I32(0), I32(0)
+    _check(load_library().marl_profile_end(ms, ctypes.byref(na), ctypes.byref(nl)), "marl_profile_end")
+    return {s: float(ms[i]) for i, s in enumerate(STAGES)}, int(na.value), int(nl.value)
+
+
+# ---- conveniences over the raw calls (allocation + marshalling only) ---------------------------
+@dataclass
+class AttnCall:
+    shape: AttnShape
+    layout: PlanLayout
+    workspace: torch.Tensor
+    out: torch.Tensor
+
+
+def prepare_attn(inp, out_dtype=MARL_OUT_BF16, suffix_chunk_tokens=0, prefix_chunk_tokens=0) -> AttnCall:
+    """Shape, workspace and output tensor for an inputs.AttnInputs resident on a GPU."""
+    shape = make_shape(inp.num_seqs, inp.num_groups, inp.Hq, inp.Hkv, inp.num_pages,
+                       int(inp.prefix_block_table.shape[1]) if inp.prefix_block_table.dim() == 2 else 0,
+                       int(inp.suffix_block_table.shape[1]) if inp.suffix_block_table.dim() == 2 else 0,
+                       out_dtype, suffix_chunk_tokens, prefix_chunk_tokens)
+    layout = marl_attn_plan_layout_for(shape)
+    dev = inp.q.device
+    ws = alloc_workspace(layout.total_bytes, dev)
+    out = torch.empty((inp.num_seqs, inp.Hq, 128), device=dev,
+                      dtype=torch.bfloat16 if out_dtype == MARL_OUT_BF16 else torch.float32)
+    return AttnCall(shape, layout, ws, out)
+
+
+def run_attn(inp, call: AttnCall) -> torch.Tensor:
+    return marl_decode_attn(call.shape, call.workspace, inp.q, inp.k_pages, inp.v_pages,
+                            inp.prefix_block_table, inp.suffix_block_table, inp.prefix_lens,
+                            inp.suffix_lens, inp.group_of_seq, inp.scale, call.out)

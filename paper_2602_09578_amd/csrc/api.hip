@@ -1,0 +1,377 @@
+// C ABI of the library: argument validation (before any HIP call), workspace layout,
+// kernel launches, optional per-kernel event timing.  See include/marl_decode.h.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "marl_internal.h"
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+int hip_fail(hipError_t e, const char* what) {
+  g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return MARL_HIP_ERROR;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+long ceil_div(long a, long b) { return (a + b - 1) / b; }
+
+int check_shape(const marl_attn_shape* s) {
+  if (!s) return MARL_INVALID_ARG;
+  if (s->num_seqs < 0 || s->num_groups < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 ||
+      s->num_pages < 1 || s->max_prefix_pages < 0 || s->max_suffix_pages < 0)
+    return MARL_INVALID_ARG;
+  if (s->num_q_heads % s->num_kv_heads != 0) return MARL_INVALID_ARG;
+  if (s->head_dim != marl::kD || s->page_size != marl::kPage) return MARL_UNSUPPORTED;
+  if (s->num_q_heads / s->num_kv_heads > 16) return MARL_UNSUPPORTED;
+  if (s->out_dtype != MARL_OUT_BF16 && s->out_dtype != MARL_OUT_F32) return MARL_UNSUPPORTED;
+  const int32_t chunks[2] = {s->suffix_chunk_tokens, s->prefix_chunk_tokens};
+  for (int32_t c : chunks)
+    if (c != 0 && (c < 32 || c > 65536 || c % 32 != 0)) return MARL_UNSUPPORTED;
+  // index arithmetic in the kernels is 32-bit for rows and tokens
+  if ((long)s->num_seqs * s->num_q_heads >= (1L << 31)) return MARL_UNSUPPORTED;
+  if ((long)s->max_prefix_pages * marl::kPage >= (1L << 30) ||
+      (long)s->max_suffix_pages * marl::kPage >= (1L << 30))
+    return MARL_UNSUPPORTED;
+  return MARL_OK;
+}
+
+int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
+  const int rc = check_shape(s);
+  if (rc != MARL_OK) return rc;
+  if (!L) return MARL_INVALID_ARG;
+  memset(L, 0, sizeof *L);
+  const long NS = s->num_seqs, NG = s->num_groups, Hkv = s->num_kv_heads, Hq = s->num_q_heads;
+  const long mst = (long)s->max_suffix_pages * marl::kPage, mpt = (long)s->max_prefix_pages * marl::kPage;
+  long Cs = s->suffix_chunk_tokens;
+  if (Cs == 0) {
+    Cs = 2048;
+    while (NS * Hkv * ceil_div(mst, Cs) < 2048 && Cs > 256) Cs /= 2;
+  }
+  long Cp = s->prefix_chunk_tokens;
+  if (Cp == 0) {
+    Cp = 1024;
+    while (NG * Hkv * ceil_div(mpt, Cp) < 1024 && Cp > 256) Cp /= 2;
+  }
+  const long NCs = ceil_div(mst, Cs) > 1 ? ceil_div(mst, Cs) : 1;
+  const long NCp = ceil_div(mpt, Cp) > 1 ? ceil_div(mpt, Cp) : 1;
+  const long R = Hq / Hkv;
+  const long max_s_items = NS * NCs;
+  const long max_p_items = (NG + NS * R / marl::kRowsPerQBlock + 1) * NCp;
+  if (max_s_items >= (1L << 28) || max_p_items >= (1L << 28)) return MARL_UNSUPPORTED;
+  L->suffix_chunk_tokens = (int32_t)Cs;
+  L->prefix_chunk_tokens = (int32_t)Cp;
+  L->suffix_slots = (int32_t)NCs;
+  L->prefix_slots = (int32_t)NCp;
+  L->rows_per_qblock = marl::kRowsPerQBlock;
+  L->max_suffix_items = (int32_t)max_s_items;
+  L->max_prefix_items = (int32_t)max_p_items;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L->counters_off = take(64 * sizeof(int32_t));
+  L->group_count_off = take((size_t)NG * 4);
+  L->group_start_off = take((size_t)(NG + 1) * 4);
+  L->seq_rank_off = take((size_t)NS * 4);
+  L->group_seqs_off = take((size_t)NS * 4);
+  L->suffix_items_off = take((size_t)max_s_items * 16);
+  L->prefix_items_off = take((size_t)max_p_items * 16);
+  L->partial_ml_off = take((size_t)NS * Hq * (NCp + NCs) * 8);
+  L->partial_o_off = take((size_t)NS * Hq * (NCp + NCs) * marl::kD * 4);
+  L->total_bytes = off;
+  return MARL_OK;
+}
+
+// ---- per-kernel event timing ---------------------------------------------------------------
+struct Profile {
+  std::mutex mu;
+  bool on = false;
+  int max_calls = 0;
+  struct Span { hipEvent_t a, b; int stage; };
+  std::vector<Span> spans;
+  int attn_calls = 0, lp_calls = 0;
+} g_prof;
+
+struct StageTimer {
+  hipStream_t st;
+  bool on;
+  explicit StageTimer(hipStream_t s, bool enabled) : st(s), on(enabled) {}
+  template <class F>
+  hipError_t run(int stage, F&& launch) {
+    if (!on) return launch();
+    Profile::Span sp{nullptr, nullptr, stage};
+    if (hipEventCreate(&sp.a) != hipSuccess || hipEventCreate(&sp.b) != hipSuccess) return launch();
+    (void)hipEventRecord(sp.a, st);
+    const hipError_t e = launch();
+    (void)hipEventRecord(sp.b, st);
+    g_prof.spans.push_back(sp);
+    return e;
+  }
+};
+
+int g_num_cus = 0, g_prefix_bpc = 0, g_suffix_bpc = 0;
+std::once_flag g_dev_once;
+hipError_t g_dev_err = hipSuccess;
+
+void query_device() {
+  int dev = 0;
+  g_dev_err = hipGetDevice(&dev);
+  if (g_dev_err != hipSuccess) return;
+  hipDeviceProp_t p;
+  g_dev_err = hipGetDeviceProperties(&p, dev);
+  if (g_dev_err != hipSuccess) return;
+  g_num_cus = p.multiProcessorCount;
+  g_prefix_bpc = marl::prefix_blocks_per_cu();
+  g_suffix_bpc = marl::suffix_blocks_per_cu();
+}
+
+int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArgs& a) {
+  marl_attn_plan_layout L;
+  const int rc = make_layout(s, &L);
+  if (rc != MARL_OK) return rc;
+  if (!ws) return MARL_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return MARL_INVALID_ARG;
+  if (ws_bytes < L.total_bytes) return MARL_WORKSPACE_TOO_SMALL;
+  char* w = static_cast<char*>(ws);
+  memset(&a, 0, sizeof a);
+  a.counters = reinterpret_cast<int32_t*>(w + L.counters_off);
+  a.group_count = reinterpret_cast<int32_t*>(w + L.group_count_off);
+  a.group_start = reinterpret_cast<int32_t*>(w + L.group_start_off);
+  a.seq_rank = reinterpret_cast<int32_t*>(w + L.seq_rank_off);
+  a.group_seqs = reinterpret_cast<int32_t*>(w + L.group_seqs_off);
+  a.suffix_items = reinterpret_cast<int4*>(w + L.suffix_items_off);
+  a.prefix_items = reinterpret_cast<int4*>(w + L.prefix_items_off);
+  a.partial_ml = reinterpret_cast<float2*>(w + L.partial_ml_off);
+  a.partial_o = reinterpret_cast<float*>(w + L.partial_o_off);
+  a.NS = s->num_seqs;
+  a.NG = s->num_groups;
+  a.Hq = s->num_q_heads;
+  a.Hkv = s->num_kv_heads;
+  a.R = a.Hq / a.Hkv;
+  a.num_pages = s->num_pages;
+  a.max_pp = s->max_prefix_pages;
+  a.max_sp = s->max_suffix_pages;
+  a.Cs = L.suffix_chunk_tokens;
+  a.Cp = L.prefix_chunk_tokens;
+  a.NCs = L.suffix_slots;
+  a.NCp = L.prefix_slots;
+  a.out_dtype = s->out_dtype;
+  return MARL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int marl_version(void) { return 1; }
+
+const char* marl_status_string(int status) {
+  switch (status) {
+    case MARL_OK: return "ok";
+    case MARL_INVALID_ARG: return "invalid argument";
+    case MARL_UNSUPPORTED: return "unsupported shape or option";
+    case MARL_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MARL_HIP_ERROR: return "HIP error";
+    default: return "unknown status";
+  }
+}
+
+const char* marl_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+int marl_attn_plan_layout_for(const marl_attn_shape* shape, marl_attn_plan_layout* layout) {
+  return make_layout(shape, layout);
+}
+
+int marl_workspace_bytes(const marl_attn_shape* shape, size_t* bytes) {
+  if (!bytes) return MARL_INVALID_ARG;
+  marl_attn_plan_layout L;
+  const int rc = make_layout(shape, &L);
+  if (rc != MARL_OK) return rc;
+  *bytes = L.total_bytes;
+  return MARL_OK;
+}
+
+int marl_attn_plan(const marl_attn_shape* shape, void* workspace, size_t workspace_bytes,
+                   const int32_t* prefix_lens, const int32_t* suffix_lens,
+                   const int32_t* group_of_seq, void* stream) {
+  marl::AttnArgs a;
+  const int rc = fill_args(shape, workspace, workspace_bytes, a);
+  if (rc != MARL_OK) return rc;
+  if ((a.NG > 0 && !prefix_lens) || (a.NS > 0 && (!suffix_lens || !group_of_seq))) return MARL_INVALID_ARG;
+  a.prefix_lens = prefix_lens;
+  a.suffix_lens = suffix_lens;
+  a.group_of_seq = group_of_seq;
+  const hipError_t e = marl::launch_plan(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "plan kernel");
+}
+
+int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t workspace_bytes,
+                     const void* q, const void* k_pages, const void* v_pages,
+                     const int32_t* prefix_block_table, const int32_t* suffix_block_table,
+                     const int32_t* prefix_lens, const int32_t* suffix_lens,
+                     const int32_t* group_of_seq, float scale, void* out, void* stream) {
+  marl::AttnArgs a;
+  const int rc = fill_args(shape, workspace, workspace_bytes, a);
+  if (rc != MARL_OK) return rc;
+  if (!isfinite(scale)) return MARL_INVALID_ARG;
+  if (a.NS > 0 && (!q || !out || !suffix_lens || !group_of_seq || !k_pages || !v_pages)) return MARL_INVALID_ARG;
+  if (a.NS > 0 && a.max_sp > 0 && !suffix_block_table) return MARL_INVALID_ARG;
+  if (a.NG > 0 && (!prefix_lens || (a.max_pp > 0 && !prefix_block_table))) return MARL_INVALID_ARG;
+  if (a.NS == 0) return MARL_OK;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_pages = static_cast<const uint16_t*>(k_pages);
+  a.v_pages = static_cast<const uint16_t*>(v_pages);
+  a.prefix_table = prefix_block_table;
+  a.suffix_table = suffix_block_table;
+  a.prefix_lens = prefix_lens;
+  a.suffix_lens = suffix_lens;
+  a.group_of_seq = group_of_seq;
+  a.scale = scale;
+  a.out = out;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  std::call_once(g_dev_once, query_device);
+  if (g_dev_err != hipSuccess) return hip_fail(g_dev_err, "device query");
+
+  std::unique_lock<std::mutex> lock(g_prof.mu, std::defer_lock);
+  bool timed = false;
+  if (g_prof.on) {
+    lock.lock();
+    timed = g_prof.on && g_prof.attn_calls < g_prof.max_calls;
+    if (timed) ++g_prof.attn_calls; else lock.unlock();
+  }
+  StageTimer T(st, timed);
+  hipError_t e;
+  if ((e = T.run(MARL_STAGE_PLAN, [&] { return marl::launch_plan(a, st); })) != hipSuccess)
+    return hip_fail(e, "plan kernel");
+  if (a.NG > 0 && a.max_pp > 0) {
+    if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * g_prefix_bpc, st); })) != hipSuccess)
+      return hip_fail(e, "prefix kernel");
+  }
+  if (a.max_sp > 0) {
+    if ((e = T.run(MARL_STAGE_SUFFIX, [&] { return marl::launch_suffix(a, g_num_cus * g_suffix_bpc, st); })) != hipSuccess)
+      return hip_fail(e, "suffix kernel");
+  }
+  if ((e = T.run(MARL_STAGE_MERGE, [&] { return marl::launch_merge(a, st); })) != hipSuccess)
+    return hip_fail(e, "merge kernel");
+  return MARL_OK;
+}
+
+int marl_attn_read_flags(const void* workspace, int32_t* flags_host, void* stream) {
+  if (!workspace || !flags_host) return MARL_INVALID_ARG;
+  const int32_t* ctr = static_cast<const int32_t*>(workspace);   // counters sit at offset 0
+  hipError_t e = hipMemcpyAsync(flags_host, ctr + MARL_CTR_FLAGS, sizeof(int32_t), hipMemcpyDeviceToHost,
+                                static_cast<hipStream_t>(stream));
+  if (e == hipSuccess) e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "read flags");
+}
+
+// ---- log-probabilities ------------------------------------------------------------------------
+static int logprob_split(int32_t rows, int32_t vocab, int32_t* slices, int32_t* slice_len) {
+  if (rows < 0 || vocab < 1) return MARL_INVALID_ARG;
+  long want = rows > 0 ? (2048 + rows - 1) / rows : 1;     // aim for >= 2048 workgroups
+  long len = (vocab + want - 1) / want;
+  if (len < 8192) len = 8192;                              // but keep slices worth a workgroup
+  len = (len + 2047) / 2048 * 2048;
+  *slice_len = (int32_t)(len > vocab ? ((long)vocab + 7) / 8 * 8 : len);
+  *slices = (int32_t)(((long)vocab + *slice_len - 1) / *slice_len);
+  return MARL_OK;
+}
+
+int marl_logprobs_workspace_bytes(int32_t rows, int32_t vocab, size_t* bytes) {
+  if (!bytes) return MARL_INVALID_ARG;
+  int32_t slices, slice_len;
+  const int rc = logprob_split(rows, vocab, &slices, &slice_len);
+  if (rc != MARL_OK) return rc;
+  *bytes = slices > 1 ? (size_t)rows * slices * sizeof(float2) : 0;
+  return MARL_OK;
+}
+
+int marl_token_logprobs(const void* logits, const int32_t* tokens, float temperature, float* out,
+                        int32_t rows, int32_t vocab, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  marl::LogprobArgs a;
+  memset(&a, 0, sizeof a);
+  const int rc = logprob_split(rows, vocab, &a.slices, &a.slice_len);
+  if (rc != MARL_OK) return rc;
+  if (!isfinite(temperature) || !(temperature > 0.f)) return MARL_INVALID_ARG;
+  if ((long)rows * a.slices >= (1L << 31)) return MARL_UNSUPPORTED;
+  if (rows == 0) return MARL_OK;
+  if (!logits || !tokens || !out) return MARL_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(logits) % 2 != 0) return MARL_INVALID_ARG;
+  const size_t need = a.slices > 1 ? (size_t)rows * a.slices * sizeof(float2) : 0;
+  if (need > 0) {
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 8 != 0) return MARL_INVALID_ARG;
+    if (workspace_bytes < need) return MARL_WORKSPACE_TOO_SMALL;
+  }
+  a.logits = static_cast<const uint16_t*>(logits);
+  a.tokens = tokens;
+  a.out = out;
+  a.partials = static_cast<float2*>(workspace);
+  a.rows = rows;
+  a.vocab = vocab;
+  a.inv_temp_log2e = 1.44269504088896340736f / temperature;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  std::unique_lock<std::mutex> lock(g_prof.mu, std::defer_lock);
+  bool timed = false;
+  if (g_prof.on) {
+    lock.lock();
+    timed = g_prof.on && g_prof.lp_calls < g_prof.max_calls;
+    if (timed) ++g_prof.lp_calls; else lock.unlock();
+  }
+  StageTimer T(st, timed);
+  hipError_t e;
+  if ((e = T.run(MARL_STAGE_LOGPROB, [&] { return marl::launch_logprobs(a, st); })) != hipSuccess)
+    return hip_fail(e, "logprob kernel");
+  if (a.slices > 1) {
+    if ((e = T.run(MARL_STAGE_LOGPROB_FINISH, [&] { return marl::launch_logprobs_finish(a, st); })) != hipSuccess)
+      return hip_fail(e, "logprob finish kernel");
+  }
+  return MARL_OK;
+}
+
+// ---- profiling ----------------------------------------------------------------------------------
+int marl_profile_begin(int32_t max_calls) {
+  if (max_calls < 1 || max_calls > (1 << 20)) return MARL_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  for (auto& sp : g_prof.spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+  g_prof.spans.clear();
+  g_prof.attn_calls = g_prof.lp_calls = 0;
+  g_prof.max_calls = max_calls;
+  g_prof.on = true;
+  return MARL_OK;
+}
+
+int marl_profile_end(float stage_ms[MARL_NUM_STAGES], int32_t* attn_calls, int32_t* logprob_calls) {
+  if (!stage_ms) return MARL_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  g_prof.on = false;
+  for (int i = 0; i < MARL_NUM_STAGES; ++i) stage_ms[i] = 0.f;
+  int rc = MARL_OK;
+  if (!g_prof.spans.empty()) {
+    const hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) rc = hip_fail(e, "profile sync");
+  }
+  double sum[MARL_NUM_STAGES] = {0};
+  for (auto& sp : g_prof.spans) {
+    float ms = 0.f;
+    if (rc == MARL_OK && hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) sum[sp.stage] += ms;
+    (void)hipEventDestroy(sp.a);
+    (void)hipEventDestroy(sp.b);
+  }
+  g_prof.spans.clear();
+  for (int i = 0; i < MARL_NUM_STAGES; ++i) {
+    const int n = i <= MARL_STAGE_MERGE ? g_prof.attn_calls : g_prof.lp_calls;
+    stage_ms[i] = n > 0 ? (float)(sum[i] / n) : 0.f;
+  }
+  if (attn_calls) *attn_calls = g_prof.attn_calls;
+  if (logprob_calls) *logprob_calls = g_prof.lp_calls;
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,337 @@
+// Decode attention over the paged KV cache: the prefix kernel (a group's prefix KV is
+// streamed once and applied to all of the group's query rows) and the suffix kernel (each
+// sequence's own generated tokens).  Both produce flash-decoding style partials
+// (running max, running sum, unnormalised output) per (query row, chunk of tokens), which
+// the merge kernel combines.
+//
+// Context in the paper: rollout is memory-bound on KV caches (Section 4.1), every prompt is
+// expanded into several samples that share its prefix (Section 5.1) and lengths are skewed
+// (Section 2.2); the paper gives no kernel, so the design below is this library's own.
+//
+// Wave-level scheme (gfx950, wave64, v_mfma_f32_16x16x32_bf16).  A wave handles 32 tokens
+// (two pages) per step and up to MT tiles of 16 query rows.  Lane l = 16*j + i.
+//   scores:  D[token-row][q-row] = K-tile (A operand) x Q^T (B operand).  A-row i of tile T
+//            is the token 8*(i/4) + 4*T + i%4 of the 32, so that after both tiles lane
+//            (i, j) holds the scores of q-row i for tokens 8j..8j+7: exactly the B operand
+//            layout the second product needs, with no data movement.
+//   output:  D[channel][q-row] += V^T-tile (A operand) x P^T (B operand), 8 channel tiles.
+//            V pages are stored [channel][slot], so lane (i, j) loads its 8 tokens of
+//            channel 16*ct + i with one 16-byte load.
+// K and V go straight from global memory into MFMA operand registers (16-byte loads; per
+// instruction a wave reads 16 x 64 B of K or 2 x 512 B of V); LDS is only used to combine
+// the four waves of a workgroup, which split the item's tokens between them.
+#include "marl_internal.h"
+
+namespace marl {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+constexpr int kWaves = kAttnThreads / 64;
+
+// LDS per workgroup: (max, sum) of every wave and one buffer for a wave's accumulators.
+template <int MT>
+struct ItemLds {
+  float m[kWaves][MT * 16];
+  float l[kWaves][MT * 16];
+  f32x4 acc[MT * 8 * 64];
+};
+
+// Processes tokens [tok_begin, tok_end) of one block-table row for MT tiles of query rows
+// and writes one partial per valid row.  Called by all four waves of the workgroup.
+//   row_index[qt]: for this lane's q-row (i) of tile qt, seq*Hq + head, or -1 if the row
+//   does not exist.  slot: partial slot of this chunk.
+template <int MT>
+__device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* __restrict__ table_row,
+                                             const int tok_begin, const int tok_end, const int kvh,
+                                             const int (&row_index)[MT], const int slot,
+                                             ItemLds<MT>& lds, int& bad_page) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 15, j = lane >> 4;
+  const float sc = fabsf(a.scale) * 1.44269504088896340736f;   // scores are kept in log2 units
+  const uint32_t sign_flip = a.scale < 0.f ? 0x80008000u : 0u;
+  const int nslot = a.NCp + a.NCs;
+
+  // Q^T operand: lane (i, j) holds channels 8*(4*kk + j) .. +8 of q-row i
+  u32x4 qreg[MT][4];
+#pragma unroll
+  for (int qt = 0; qt < MT; ++qt) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (row_index[qt] >= 0) {
+        v = *reinterpret_cast<const u32x4*>(a.q + (size_t)row_index[qt] * kD + (4 * kk + j) * 8);
+        v ^= sign_flip;
+      }
+      qreg[qt][kk] = v;
+    }
+  }
+
+  f32x4 acc[MT][8];
+  float m_run[MT], l_run[MT];
+#pragma unroll
+  for (int qt = 0; qt < MT; ++qt) {
+    m_run[qt] = -INFINITY;
+    l_run[qt] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
+  const char* kbase = reinterpret_cast<const char*>(a.k_pages) + (size_t)kvh * (kPage * kD * 2) +
+                      ((8 * ((i >> 2) & 1) + (i & 3)) * (kD * 2) + j * 16);
+  const char* vbase = reinterpret_cast<const char*>(a.v_pages) + (size_t)kvh * (kPage * kD * 2) +
+                      (i * (kPage * 2) + (j & 1) * 16);
+
+  for (int t0 = tok_begin + wave * kBlockTok; t0 < tok_end; t0 += kWaves * kBlockTok) {
+    int p0 = table_row[t0 >> 4];
+    int p1 = (t0 + kPage < tok_end) ? table_row[(t0 >> 4) + 1] : p0;
+    if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
+    if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
+    const char* kp = kbase + (size_t)(i < 8 ? p0 : p1) * page_bytes;
+    const char* vp = vbase + (size_t)(j < 2 ? p0 : p1) * page_bytes;
+
+    u32x4 kr[2][4], vr[8];
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        kr[T][kk] = *reinterpret_cast<const u32x4*>(kp + T * (4 * kD * 2) + kk * 64);
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) vr[ct] = *reinterpret_cast<const u32x4*>(vp + ct * (16 * kPage * 2));
+
+    const bool ragged = t0 + kBlockTok > tok_end;   // wave-uniform
+    if (ragged) {
+      // zero the value slots no token owns (they may hold anything, NaN included)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const int tok = t0 + 8 * j + 2 * d;
+        const uint32_t mask = (tok < tok_end ? 0x0000ffffu : 0u) | (tok + 1 < tok_end ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) vr[ct][d] &= mask;
+      }
+    }
+
+#pragma unroll
+    for (int qt = 0; qt < MT; ++qt) {
+      f32x4 s[2];
+#pragma unroll
+      for (int T = 0; T < 2; ++T) {
+        s[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) s[T] = mfma_16x16x32(kr[T][kk], qreg[qt][kk], s[T]);
+      }
+      bool valid[2][4];
+#pragma unroll
+      for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          valid[T][e] = !ragged || (t0 + 8 * j + 4 * T + e < tok_end);
+          if (!valid[T][e]) s[T][e] = -INFINITY;
+        }
+      float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                       fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[qt], mx * sc);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+      float p[2][4];
+      float psum = 0.f;
+#pragma unroll
+      for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float v = __builtin_amdgcn_exp2f(__builtin_fmaf(s[T][e], sc, -m_new));
+          if (!valid[T][e]) v = 0.f;
+          p[T][e] = v;
+          psum += v;
+        }
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run[qt]) != 0) {   // wave-uniform
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= alpha;
+      }
+      l_run[qt] = l_run[qt] * alpha + psum;
+      m_run[qt] = m_new;
+      const u32x4 pb = {pack_bf16(p[0][0], p[0][1]), pack_bf16(p[0][2], p[0][3]),
+                        pack_bf16(p[1][0], p[1][1]), pack_bf16(p[1][2], p[1][3])};
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = mfma_16x16x32(vr[ct], pb, acc[qt][ct]);
+    }
+  }
+
+  // the four lanes that share a q-row each hold a part of its sum
+#pragma unroll
+  for (int qt = 0; qt < MT; ++qt) {
+    l_run[qt] += __shfl_xor(l_run[qt], 16);
+    l_run[qt] += __shfl_xor(l_run[qt], 32);
+  }
+
+  // combine the waves in a fixed order: every wave rescales to the common max, then waves
+  // 1..3 hand their accumulators to wave 0 one after the other
+  if (j == 0) {
+#pragma unroll
+    for (int qt = 0; qt < MT; ++qt) {
+      lds.m[wave][qt * 16 + i] = m_run[qt];
+      lds.l[wave][qt * 16 + i] = l_run[qt];
+    }
+  }
+  __syncthreads();
+  float m_all[MT], l_all[MT];
+#pragma unroll
+  for (int qt = 0; qt < MT; ++qt) {
+    float mm = lds.m[0][qt * 16 + i];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, lds.m[w][qt * 16 + i]);
+    float ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float mw = lds.m[w][qt * 16 + i];
+      const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
+      ll += lds.l[w][qt * 16 + i] * f;
+    }
+    m_all[qt] = mm;
+    l_all[qt] = ll;
+    const float f_own = (m_run[qt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[qt] - mm);
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= f_own;
+  }
+  for (int w = 1; w < kWaves; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int qt = 0; qt < MT; ++qt)
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) lds.acc[(qt * 8 + ct) * 64 + lane] = acc[qt][ct];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int qt = 0; qt < MT; ++qt)
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[qt][ct] += lds.acc[(qt * 8 + ct) * 64 + lane];
+    }
+    __syncthreads();
+  }
+
+  if (wave == 0) {
+#pragma unroll
+    for (int qt = 0; qt < MT; ++qt) {
+      if (row_index[qt] >= 0) {
+        const size_t ps = (size_t)row_index[qt] * nslot + slot;
+        float* dst = a.partial_o + ps * kD + 4 * j;
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct];
+        if (j == 0) a.partial_ml[ps] = make_float2(m_all[qt], l_all[qt]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Suffix kernel: one work item = (sequence, chunk of its generated tokens, KV head); the
+// R = Hq/Hkv query heads of that KV head are the (zero-padded) 16-row tile.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAttnThreads) void suffix_kernel(AttnArgs a) {
+  __shared__ ItemLds<1> lds;
+  __shared__ int next_item;
+  const int n_work = a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] * a.Hkv;
+  int bad_page = 0;
+  for (;;) {
+    if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_SUFFIX_CURSOR], 1);
+    __syncthreads();
+    const int qi = next_item;
+    __syncthreads();
+    if (qi >= n_work) break;
+    const int4 it = a.suffix_items[qi / a.Hkv];
+    const int kvh = qi % a.Hkv;
+    const int s = it.x;
+    const int i = threadIdx.x & 15;
+    const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
+    process_item<1>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
+                    a.NCp + it.y / a.Cs, lds, bad_page);
+  }
+  if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
+}
+
+// ---------------------------------------------------------------------------------------
+// Prefix kernel: one work item = (group, chunk of prefix tokens, block of up to 64 query
+// rows, KV head).  Query row rho of a group is (its rho / R -th sequence, head kvh*R + rho % R).
+// ---------------------------------------------------------------------------------------
+template <int MT>
+__device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, const int kvh,
+                                            ItemLds<4>& lds, int& bad_page) {
+  const int g = it.x;
+  const int gstart = a.group_start[g];
+  const int nrows = a.group_count[g] * a.R;
+  const int i = threadIdx.x & 15;
+  int row_index[MT];
+#pragma unroll
+  for (int qt = 0; qt < MT; ++qt) {
+    const int rho = it.w + qt * 16 + i;
+    int idx = -1;
+    if (rho < nrows) idx = a.group_seqs[gstart + rho / a.R] * a.Hq + kvh * a.R + rho % a.R;
+    row_index[qt] = idx;
+  }
+  process_item<MT>(a, a.prefix_table + (size_t)g * a.max_pp, it.y, it.z, kvh, row_index,
+                   it.y / a.Cp, reinterpret_cast<ItemLds<MT>&>(lds), bad_page);
+}
+
+__global__ __launch_bounds__(kAttnThreads) void prefix_kernel(AttnArgs a) {
+  __shared__ ItemLds<4> lds;
+  __shared__ int next_item;
+  const int n_work = a.counters[MARL_CTR_NUM_PREFIX_ITEMS] * a.Hkv;
+  int bad_page = 0;
+  for (;;) {
+    if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_PREFIX_CURSOR], 1);
+    __syncthreads();
+    const int qi = next_item;
+    __syncthreads();
+    if (qi >= n_work) break;
+    const int4 it = a.prefix_items[qi / a.Hkv];
+    const int kvh = qi % a.Hkv;
+    const int rows = min(kRowsPerQBlock, a.group_count[it.x] * a.R - it.w);
+    const int mt = (rows + 15) >> 4;   // workgroup-uniform
+    if (mt <= 1) prefix_item<1>(a, it, kvh, lds, bad_page);
+    else if (mt == 2) prefix_item<2>(a, it, kvh, lds, bad_page);
+    else if (mt == 3) prefix_item<3>(a, it, kvh, lds, bad_page);
+    else prefix_item<4>(a, it, kvh, lds, bad_page);
+  }
+  if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
+}
+
+}  // namespace
+
+int prefix_blocks_per_cu() {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, prefix_kernel, kAttnThreads, 0) != hipSuccess || n < 1) n = 1;
+  return n;
+}
+int suffix_blocks_per_cu() {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, suffix_kernel, kAttnThreads, 0) != hipSuccess || n < 1) n = 1;
+  return n;
+}
+
+hipError_t launch_prefix(const AttnArgs& a, int grid, hipStream_t st) {
+  hipLaunchKernelGGL(prefix_kernel, dim3(grid), dim3(kAttnThreads), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st) {
+  hipLaunchKernelGGL(suffix_kernel, dim3(grid), dim3(kAttnThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace marl

@@ -1,0 +1,63 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "marl_decode.h"
+
+namespace marl {
+
+constexpr int kPage = 16;        // tokens per page
+constexpr int kD = 128;          // head dimension
+constexpr int kBlockTok = 32;    // tokens one MFMA step of a wave covers (two pages)
+constexpr int kRowsPerQBlock = 64;
+constexpr int kAttnThreads = 256;  // 4 waves per workgroup
+constexpr int kPlanThreads = 1024;
+constexpr int kNumClasses = 2048;  // upper bound on cost classes (chunk / 32)
+
+// Everything the attention kernels need; passed by value.
+struct AttnArgs {
+  const uint16_t* q;
+  const uint16_t* k_pages;
+  const uint16_t* v_pages;
+  const int32_t* prefix_table;
+  const int32_t* suffix_table;
+  const int32_t* prefix_lens;
+  const int32_t* suffix_lens;
+  const int32_t* group_of_seq;
+  int32_t* counters;
+  int32_t* group_count;
+  int32_t* group_start;
+  int32_t* seq_rank;
+  int32_t* group_seqs;
+  int4* suffix_items;
+  int4* prefix_items;
+  float2* partial_ml;
+  float* partial_o;
+  void* out;
+  int32_t NS, NG, Hq, Hkv, R;
+  int32_t num_pages, max_pp, max_sp;
+  int32_t Cs, Cp, NCs, NCp;
+  int32_t out_dtype;
+  float scale;
+};
+
+hipError_t launch_plan(const AttnArgs& a, hipStream_t st);
+hipError_t launch_prefix(const AttnArgs& a, int grid, hipStream_t st);
+hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st);
+hipError_t launch_merge(const AttnArgs& a, hipStream_t st);
+int prefix_blocks_per_cu();
+int suffix_blocks_per_cu();
+
+struct LogprobArgs {
+  const uint16_t* logits;
+  const int32_t* tokens;
+  float* out;
+  float2* partials;   // [rows][slices] (max, sum) in base-2 units; unused when slices == 1
+  int32_t rows, vocab, slices, slice_len;
+  float inv_temp_log2e;   // log2(e) / T
+};
+hipError_t launch_logprobs(const LogprobArgs& a, hipStream_t st);
+hipError_t launch_logprobs_finish(const LogprobArgs& a, hipStream_t st);
+
+}  // namespace marl

@@ -1,0 +1,186 @@
+// Plan kernel: builds, on the device, the group -> sequences CSR and the two work lists of
+// one decode-attention call, so that sequence lengths never travel to the host.
+//
+// Why a work list at all: rollout load is heavily skewed across agents (the paper's
+// Observation #2, Section 2.2) and response lengths have a long tail (Observation #1), so
+// work is cut into token-sized items and listed longest first; the attention kernels then
+// pull items from the list in order.  The rule is the one documented in marl_decode.h.
+//
+// One workgroup of 1024 threads; all of it is integer work.  Item order inside one cost
+// class depends on atomics and may differ between runs; it only decides which workgroup
+// processes an item, never a numerical result (every item owns its partial slot).
+#include "marl_internal.h"
+
+namespace marl {
+namespace {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// Read of a value another thread of this kernel wrote to global memory: bypasses the
+// per-CU vector cache, which may still hold the line from before the write.
+__device__ __forceinline__ int ld_agent(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(v, d);
+    if (lane >= d) v += t;
+  }
+  return v;
+}
+
+// out[i] = sum of in[0..i) for i < n (in and out may alias); returns the total to every
+// thread.  tmp: 17 shared ints.  Must be called by all 1024 threads.  GLOBAL_IN: `in` is
+// global memory written earlier in this kernel.
+template <bool GLOBAL_IN>
+__device__ int block_exclusive_scan(const int* in, int* out, int n, int* tmp) {
+  int carry = 0;
+  for (int base = 0; base < n; base += kPlanThreads) {
+    const int i = base + threadIdx.x;
+    const int v = i < n ? (GLOBAL_IN ? ld_agent(in + i) : in[i]) : 0;
+    const int inc = wave_inclusive_scan(v);
+    if (lane_id() == 63) tmp[wave_id()] = inc;
+    __syncthreads();
+    if (wave_id() == 0) {
+      const int t = lane_id() < 16 ? tmp[lane_id()] : 0;
+      const int ti = wave_inclusive_scan(t);
+      if (lane_id() < 16) tmp[lane_id()] = ti - t;
+      if (lane_id() == 15) tmp[16] = ti;
+    }
+    __syncthreads();
+    if (i < n) out[i] = carry + tmp[wave_id()] + inc - v;
+    carry += tmp[16];
+    __syncthreads();
+  }
+  return carry;
+}
+
+__device__ __forceinline__ int clamp_len(int v, int hi, int& flags) {
+  const int c = min(max(v, 0), hi);
+  if (c != v) flags |= MARL_FLAG_LEN_CLAMPED;
+  return c;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
+  __shared__ int hist_s[kNumClasses];
+  __shared__ int hist_p[kNumClasses];
+  __shared__ int tmp[17];
+  const int tid = threadIdx.x;
+  const int Cs = a.Cs, Cp = a.Cp, R = a.R;
+  const int ncls_s = Cs / 32, ncls_p = Cp / 32;
+  const int max_st = a.max_sp * kPage, max_pt = a.max_pp * kPage;
+  int flags = 0;
+
+  for (int i = tid; i < kNumClasses; i += kPlanThreads) { hist_s[i] = 0; hist_p[i] = 0; }
+  for (int g = tid; g < a.NG; g += kPlanThreads) a.group_count[g] = 0;
+  if (tid < 64) a.counters[tid] = 0;
+  __threadfence();
+  __syncthreads();
+
+  // sequences: rank inside the group, histogram of suffix items by cost class
+  for (int s = tid; s < a.NS; s += kPlanThreads) {
+    const int g = a.group_of_seq[s];
+    int rank = -1;
+    if ((unsigned)g < (unsigned)a.NG) rank = atomicAdd(&a.group_count[g], 1);
+    else flags |= MARL_FLAG_BAD_GROUP;
+    a.seq_rank[s] = rank;
+    const int S = clamp_len(a.suffix_lens[s], max_st, flags);
+    const int nfull = S / Cs, tail = S % Cs;
+    if (nfull) atomicAdd(&hist_s[0], nfull);
+    if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
+  }
+  __threadfence();
+  __syncthreads();
+
+  // CSR offsets
+  const int nseq_grouped = block_exclusive_scan<true>(a.group_count, a.group_start, a.NG, tmp);
+  if (tid == 0) a.group_start[a.NG] = nseq_grouped;
+
+  // groups: histogram of prefix items (one per chunk and per block of 64 query rows)
+  for (int g = tid; g < a.NG; g += kPlanThreads) {
+    const int P = clamp_len(a.prefix_lens[g], max_pt, flags);
+    const int nqb = (ld_agent(a.group_count + g) * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+    const int nfull = P / Cp, tail = P % Cp;
+    if (nqb) {
+      if (nfull) atomicAdd(&hist_p[0], nfull * nqb);
+      if (tail) atomicAdd(&hist_p[(Cp - tail) / 32], nqb);
+    }
+  }
+  __threadfence();
+  __syncthreads();
+
+  // class start offsets; afterwards the histograms serve as per-class cursors
+  const int n_suffix_items = block_exclusive_scan<false>(hist_s, hist_s, ncls_s, tmp);
+  const int n_prefix_items = block_exclusive_scan<false>(hist_p, hist_p, ncls_p, tmp);
+
+  for (int s = tid; s < a.NS; s += kPlanThreads) {
+    const int rank = a.seq_rank[s];
+    if (rank >= 0) a.group_seqs[ld_agent(a.group_start + a.group_of_seq[s]) + rank] = s;
+    int dummy = 0;
+    const int S = clamp_len(a.suffix_lens[s], max_st, dummy);
+    const int nfull = S / Cs, tail = S % Cs;
+    if (nfull) {
+      const int pos = atomicAdd(&hist_s[0], nfull);
+      for (int i = 0; i < nfull; ++i) a.suffix_items[pos + i] = make_int4(s, i * Cs, (i + 1) * Cs, 0);
+    }
+    if (tail) {
+      const int pos = atomicAdd(&hist_s[(Cs - tail) / 32], 1);
+      a.suffix_items[pos] = make_int4(s, nfull * Cs, S, 0);
+    }
+  }
+  for (int g = tid; g < a.NG; g += kPlanThreads) {
+    int dummy = 0;
+    const int P = clamp_len(a.prefix_lens[g], max_pt, dummy);
+    const int nqb = (ld_agent(a.group_count + g) * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+    const int nfull = P / Cp, tail = P % Cp;
+    if (nqb) {
+      if (nfull) {
+        const int pos = atomicAdd(&hist_p[0], nfull * nqb);
+        for (int i = 0; i < nfull; ++i)
+          for (int b = 0; b < nqb; ++b)
+            a.prefix_items[pos + i * nqb + b] = make_int4(g, i * Cp, (i + 1) * Cp, b * kRowsPerQBlock);
+      }
+      if (tail) {
+        const int pos = atomicAdd(&hist_p[(Cp - tail) / 32], nqb);
+        for (int b = 0; b < nqb; ++b)
+          a.prefix_items[pos + b] = make_int4(g, nfull * Cp, P, b * kRowsPerQBlock);
+      }
+    }
+  }
+  __threadfence();
+  __syncthreads();
+
+  // make the CSR order deterministic: ascending sequence id inside every small group
+  for (int g = tid; g < a.NG; g += kPlanThreads) {
+    const int b = ld_agent(a.group_start + g), n = ld_agent(a.group_count + g);
+    if (n <= 64) {
+      for (int i = 1; i < n; ++i) {
+        const int v = ld_agent(a.group_seqs + b + i);
+        int k = i - 1;
+        while (k >= 0 && ld_agent(a.group_seqs + b + k) > v) {
+          a.group_seqs[b + k + 1] = ld_agent(a.group_seqs + b + k);
+          --k;
+        }
+        a.group_seqs[b + k + 1] = v;
+      }
+    }
+  }
+  if (flags) atomicOr(&a.counters[MARL_CTR_FLAGS], flags);
+  if (tid == 0) {
+    a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] = n_suffix_items;
+    a.counters[MARL_CTR_NUM_PREFIX_ITEMS] = n_prefix_items;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_plan(const AttnArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace marl

@@ -1,0 +1,106 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_09578_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "marl_decode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(marl_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = declared_symbols()
+    assert {"marl_decode_attn", "marl_token_logprobs", "marl_workspace_bytes", "marl_attn_plan"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.marl_version() >= 1
+
+
+def good_shape(**kw):
+    d = dict(num_seqs=16, num_groups=4, num_q_heads=8, num_kv_heads=2, num_pages=100,
+             max_prefix_pages=16, max_suffix_pages=8)
+    d.update(kw)
+    return B.make_shape(**d)
+
+
+def status_of(fn):
+    try:
+        fn()
+    except B.MarlError as e:
+        return e.status
+    return 0
+
+
+def test_layout_and_default_chunks():
+    L = B.marl_attn_plan_layout_for(good_shape())
+    assert (L.suffix_chunk_tokens, L.prefix_chunk_tokens) == (256, 256)
+    assert (L.suffix_slots, L.prefix_slots, L.rows_per_qblock) == (1, 1, 64)
+    assert L.total_bytes == B.marl_workspace_bytes(good_shape())
+    offs = [L.counters_off, L.group_count_off, L.group_start_off, L.seq_rank_off, L.group_seqs_off,
+            L.suffix_items_off, L.prefix_items_off, L.partial_ml_off, L.partial_o_off, L.total_bytes]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and offs[0] == 0
+    assert L.partial_o_off + 16 * 8 * 2 * 128 * 4 <= L.total_bytes
+    big = B.marl_attn_plan_layout_for(good_shape(num_seqs=2048, num_groups=256, num_q_heads=28, num_kv_heads=4,
+                                                 max_prefix_pages=128, max_suffix_pages=512))
+    assert (big.suffix_chunk_tokens, big.prefix_chunk_tokens, big.suffix_slots, big.prefix_slots) == (2048, 1024, 4, 2)
+    ov = B.marl_attn_plan_layout_for(good_shape(suffix_chunk_tokens=64, prefix_chunk_tokens=96))
+    assert (ov.suffix_chunk_tokens, ov.prefix_chunk_tokens, ov.suffix_slots, ov.prefix_slots) == (64, 96, 2, 3)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(num_seqs=-1), -1), (dict(num_q_heads=7), -1), (dict(num_kv_heads=0), -1), (dict(num_pages=0), -1),
+    (dict(head_dim=64), -2), (dict(page_size=32), -2), (dict(out_dtype=5), -2),
+    (dict(suffix_chunk_tokens=48), -2), (dict(prefix_chunk_tokens=16), -2),
+    (dict(num_q_heads=34, num_kv_heads=2), -2)])
+def test_bad_shapes_are_rejected_on_the_host(kw, status):
+    assert status_of(lambda: B.marl_workspace_bytes(good_shape(**kw))) == status
+
+
+def test_decode_attn_argument_errors_without_gpu():
+    lib = B.load_library()
+    shape = good_shape()
+    need = B.marl_workspace_bytes(shape)
+    buf = ctypes.create_string_buffer(need + 512)
+    base = (ctypes.addressof(buf) + 255) // 256 * 256
+    p = ctypes.c_void_p(base)
+    call = lambda ws, nbytes, q, scale: lib.marl_decode_attn(ctypes.byref(shape), ws, nbytes, q, p, p, p, p, p, p, p,
+                                                            ctypes.c_float(scale), p, None)
+    assert call(None, need, p, 1.0) == -1                      # null workspace
+    assert call(ctypes.c_void_p(base + 8), need, p, 1.0) == -1  # misaligned workspace
+    assert call(p, need - 1, p, 1.0) == -3                     # too small
+    assert call(p, need, None, 1.0) == -1                      # null q
+    assert call(p, need, p, float("nan")) == -1
+    assert call(p, need, p, float("inf")) == -1
+    assert lib.marl_decode_attn(None, p, need, p, p, p, p, p, p, p, p, ctypes.c_float(1.0), p, None) == -1
+
+
+def test_logprobs_argument_errors_without_gpu():
+    lib = B.load_library()
+    buf = ctypes.create_string_buffer(1024)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    f = lambda logits, T, rows, vocab, ws=None, n=0: lib.marl_token_logprobs(logits, p, ctypes.c_float(T), p, rows, vocab, ws, n, None)
+    assert f(p, 0.0, 4, 100) == -1 and f(p, -1.0, 4, 100) == -1 and f(p, float("nan"), 4, 100) == -1
+    assert f(None, 1.0, 4, 100) == -1
+    assert f(p, 1.0, -1, 100) == -1 and f(p, 1.0, 4, 0) == -1
+    assert f(p, 1.0, 0, 100) == 0                              # nothing to do
+    assert f(p, 1.0, 4, 152064, None, 0) == -1                 # sliced launch needs a workspace
+    assert f(p, 1.0, 4, 152064, p, 8) == -3
+    assert B.marl_logprobs_workspace_bytes(2048, 152064) == 0
+    assert B.marl_logprobs_workspace_bytes(256, 152064) == 256 * 8 * 8
+    assert lib.marl_status_string(-3) == b"workspace too small"
+
+
+def test_profile_argument_errors():
+    lib = B.load_library()
+    assert lib.marl_profile_begin(0) == -1
+    assert lib.marl_profile_end(None, None, None) == -1

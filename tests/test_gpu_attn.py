@@ -1,0 +1,169 @@
+"""GPU parity of marl_decode_attn against the float64 checker, element by element, through
+the C ABI.  Tolerance: max |delta| <= 4e-3."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_09578_amd import binding as B
+from paper_2602_09578_amd import inputs as I
+from tests.gpu_common import ATTN_TOL, check_attn, gpu_attn, oracle_attn
+
+pytestmark = pytest.mark.gpu
+
+
+def custom_inputs(prefix_lens, suffix_lens, group_of_seq, Hq, Hkv, seed, scale=None, poison=True):
+    L = I.Lengths(np.asarray(prefix_lens, np.int32), np.asarray(suffix_lens, np.int32),
+                  np.asarray(group_of_seq, np.int32), np.zeros(len(prefix_lens), np.int32))
+    w = I.Workload("custom", Hq, Hkv, (), seed)
+    inp = I.build_attn_inputs(w, "cpu", seed, poison=poison, lengths=L)
+    if scale is not None:
+        inp.scale = scale
+    return inp
+
+
+@pytest.mark.parametrize("out_dtype", [B.MARL_OUT_F32, B.MARL_OUT_BF16])
+def test_tiny_workload(out_dtype):
+    print("case: tiny", out_dtype, flush=True)
+    err = check_attn(I.build_attn_inputs(I.WORKLOADS["tiny"]), out_dtype)
+    print("max err", err)
+
+
+@pytest.mark.parametrize("name,pdiv,ldiv", [("qwen7b", 16, 4), ("skew", 8, 8), ("prefix", 16, 4),
+                                            ("long32b", 8, 8)])
+def test_scaled_workloads(name, pdiv, ldiv):
+    """The named workloads with fewer prompts and shorter lengths, so the checker finishes in
+    seconds; they still span several chunks, several query-row blocks and ragged tails."""
+    print("case:", name, pdiv, ldiv, flush=True)
+    w = I.WORKLOADS[name].scaled(pdiv, ldiv)
+    inp = I.build_attn_inputs(w)
+    err = check_attn(inp, B.MARL_OUT_BF16)
+    print(name, "seqs", inp.num_seqs, "max err", err)
+
+
+@pytest.mark.parametrize("cs,cp", [(32, 32), (64, 96), (256, 128)])
+def test_small_chunks_many_partials(cs, cp):
+    print("case: chunks", cs, cp, flush=True)
+    w = I.WORKLOADS["qwen7b"].scaled(32, 8)
+    check_attn(I.build_attn_inputs(w), B.MARL_OUT_F32, suffix_chunk_tokens=cs, prefix_chunk_tokens=cp)
+
+
+def test_edge_lengths_and_ragged_groups():
+    """Empty suffixes, empty prefixes, sequences with no token at all, lengths on and around
+    page / step / chunk boundaries, groups of different sizes listed in shuffled order."""
+    print("case: edge lengths", flush=True)
+    rng = np.random.default_rng(7)
+    plens = [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 300]
+    sizes = [1, 2, 3, 5, 8, 1, 4, 11, 2, 1, 6, 3]
+    gos = np.repeat(np.arange(len(plens)), sizes)
+    slens = rng.choice([0, 1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 513],
+                       size=len(gos))
+    slens[0] = 0                                  # group 0 has no prefix: this sequence has no token
+    perm = rng.permutation(len(gos))
+    inp = custom_inputs(plens, slens[perm], gos[perm], 12, 4, seed=3)
+    want = oracle_attn(inp)
+    got, _ = gpu_attn(inp, B.MARL_OUT_F32)
+    assert np.abs(got - want).max() <= ATTN_TOL
+    s0 = int(np.nonzero(perm == 0)[0][0])
+    assert np.all(got[s0] == 0.0)
+    got2, _ = gpu_attn(inp, B.MARL_OUT_F32, suffix_chunk_tokens=64, prefix_chunk_tokens=32)
+    assert np.abs(got2 - want).max() <= ATTN_TOL
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (16, 1), (6, 2), (64, 8)])
+def test_head_layouts(Hq, Hkv):
+    print("case: heads", Hq, Hkv, flush=True)
+    inp = custom_inputs([70, 33], [40, 5, 100, 64, 1], [0, 0, 1, 1, 1], Hq, Hkv, seed=5)
+    check_attn(inp, B.MARL_OUT_F32)
+
+
+def test_big_group_many_query_blocks():
+    """A group whose G*R rows need several 64-row blocks, the last one ragged."""
+    print("case: big group", flush=True)
+    G = 21                      # 21 * 7 = 147 rows -> blocks of 64, 64, 19
+    inp = custom_inputs([200], list(range(1, G + 1)), [0] * G, 28, 4, seed=9)
+    check_attn(inp, B.MARL_OUT_F32)
+
+
+def test_negative_and_zero_scale():
+    print("case: scale sign", flush=True)
+    for scale in (-0.11, 0.0):
+        inp = custom_inputs([50], [20, 7], [0, 0], 8, 2, seed=11, scale=scale)
+        check_attn(inp, B.MARL_OUT_F32)
+
+
+def test_reruns_and_page_permutations_are_bit_identical():
+    print("case: determinism", flush=True)
+    w = I.WORKLOADS["qwen7b"].scaled(32, 8)
+    a = I.build_attn_inputs(w, seed=100)
+    out1, call = gpu_attn(a, B.MARL_OUT_F32)
+    dev = a.to("cuda")
+    for _ in range(3):
+        B.run_attn(dev, call)
+        torch.cuda.synchronize()
+        assert np.array_equal(call.out.float().cpu().numpy().astype(np.float64), out1)
+    # same logical content on differently numbered physical pages
+    rng = np.random.default_rng(5)
+    perm = torch.from_numpy(rng.permutation(a.num_pages))
+    inv = torch.empty_like(perm); inv[perm] = torch.arange(a.num_pages)
+    b = I.AttnInputs(a.Hq, a.Hkv, a.num_pages, a.q, a.k_pages[perm], a.v_pages[perm],
+                     torch.where(a.prefix_block_table >= 0, inv[a.prefix_block_table.clamp(min=0).long()].int(), -1),
+                     torch.where(a.suffix_block_table >= 0, inv[a.suffix_block_table.clamp(min=0).long()].int(), -1),
+                     a.prefix_lens, a.suffix_lens, a.group_of_seq, a.scale)
+    out2, _ = gpu_attn(b, B.MARL_OUT_F32)
+    assert np.array_equal(out1, out2)
+
+
+def test_poison_value_does_not_matter():
+    print("case: poison", flush=True)
+    w = I.WORKLOADS["tiny"]
+    a = I.build_attn_inputs(w, poison=True)
+    b = I.build_attn_inputs(w, poison=False)     # same draws, unused locations hold ordinary numbers
+    oa, _ = gpu_attn(a, B.MARL_OUT_F32)
+    ob, _ = gpu_attn(b, B.MARL_OUT_F32)
+    assert np.isfinite(oa).all() and np.array_equal(oa, ob)
+
+
+def test_bad_device_contents_are_clamped_and_flagged():
+    """Out-of-range lengths, group ids and page ids never leave the buffers: the kernels
+    clamp them and set a flag."""
+    print("case: flags", flush=True)
+    inp = custom_inputs([40, 20], [30, 10, 25], [0, 1, 1], 8, 2, seed=13, poison=False)
+    bad = I.AttnInputs(**{**inp.__dict__})
+    bad.suffix_lens = inp.suffix_lens.clone(); bad.suffix_lens[0] = 10 ** 6
+    bad.group_of_seq = inp.group_of_seq.clone(); bad.group_of_seq[1] = 99
+    bad.suffix_block_table = inp.suffix_block_table.clone(); bad.suffix_block_table[2, 0] = 10 ** 8
+    got, _ = gpu_attn(bad, B.MARL_OUT_F32,
+                      expect_flags=B.FLAG_BAD_GROUP | B.FLAG_LEN_CLAMPED | B.FLAG_BAD_PAGE)
+    assert np.isfinite(got).all()
+
+
+def _sampled_full_size(name, n_random=6):
+    """Full-size workload in the launch configuration the benchmark uses; the checker
+    recomputes a sample of sequences (the longest, the shortest and a few random ones)."""
+    w = I.WORKLOADS[name]
+    dev = I.build_attn_inputs(w, device="cuda")
+    call = B.prepare_attn(dev, B.MARL_OUT_BF16)
+    B.run_attn(dev, call)
+    torch.cuda.synchronize()
+    assert B.marl_attn_read_flags(call.workspace) == 0
+    total = (dev.prefix_lens[dev.group_of_seq.long()] + dev.suffix_lens).cpu().numpy()
+    rng = np.random.default_rng(1)
+    pick = sorted({int(np.argmax(total)), int(np.argmin(total)), 0, len(total) - 1,
+                   *[int(x) for x in rng.integers(0, len(total), n_random)]})
+    sub = I.extract_subproblem(dev, pick)
+    want = oracle_attn(sub)
+    got = call.out[torch.tensor(pick, device="cuda")].float().cpu().numpy().astype(np.float64)
+    err = float(np.abs(got - want).max())
+    print(name, "sampled seqs", pick, "max err", err)
+    assert torch.isfinite(call.out.float()).all().item()
+    assert err <= ATTN_TOL
+    del dev, call
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["qwen7b", "skew", "prefix", "long32b"])
+def test_full_size_sampled(name):
+    print("case: full size", name, flush=True)
+    _sampled_full_size(name)
