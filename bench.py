@@ -1,0 +1,131 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout decode step on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: marl_decode_attn (plan, prefix, suffix, merge kernels) followed by
+marl_token_logprobs, on the Qwen-7B-shaped workload (2048 sequences, vocabulary 152064).
+Prints ONE JSON line.  The CPU baseline leg times the float64 checker on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2602_09578_amd import binding as B  # noqa: E402
+from paper_2602_09578_amd import inputs as I   # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def cpu_baseline(attn_dev: I.AttnInputs, lp_dev: I.LogprobInputs, seq_stride: int, lp_rows: int):
+    """Times the float64 checker (as it stands, all host threads) on every `seq_stride`-th
+    sequence and on the first `lp_rows` logit rows of the same workload."""
+    from oracle import reference as ref
+    pick = list(range(0, attn_dev.num_seqs, seq_stride))
+    sub = I.extract_subproblem(attn_dev, pick)
+    args = (I.bf16_bits(sub.q), I.bf16_bits(sub.k_pages), I.bf16_bits(sub.v_pages),
+            sub.prefix_block_table.numpy(), sub.suffix_block_table.numpy(), sub.prefix_lens.numpy(),
+            sub.suffix_lens.numpy(), sub.group_of_seq.numpy(), sub.scale, sub.Hq, sub.Hkv)
+    t0 = time.perf_counter()
+    _, threads = ref.decode_attn(*args, return_threads=True)
+    t_attn = time.perf_counter() - t0
+    rows = min(lp_rows, lp_dev.logits.shape[0])
+    lg = I.bf16_bits(lp_dev.logits[:rows])
+    tk = lp_dev.tokens[:rows].cpu().numpy()
+    t0 = time.perf_counter()
+    ref.token_logprobs(lg, tk, lp_dev.temperature)
+    t_lp = time.perf_counter() - t0
+    per_seq = t_attn / len(pick) + t_lp / rows      # one sequence's attention + its log-prob row
+    return {"value": 1.0 / per_seq, "unit": "sequences*steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"every {seq_stride}th sequence ({len(pick)} of {attn_dev.num_seqs}) for attention "
+                      f"({t_attn:.2f} s) and {rows} of {lp_dev.logits.shape[0]} logit rows ({t_lp:.2f} s)",
+            "attn_seqs_per_s": len(pick) / t_attn, "logprob_rows_per_s": rows / t_lp}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen7b", choices=sorted(I.WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--suffix-chunk", type=int, default=0)
+    ap.add_argument("--prefix-chunk", type=int, default=0)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU: the library has no CPU path")
+
+    w = I.WORKLOADS[a.workload]
+    dev = torch.device("cuda:0")
+    attn = I.build_attn_inputs(w, device=dev)
+    call = B.prepare_attn(attn, B.MARL_OUT_BF16, a.suffix_chunk, a.prefix_chunk)
+    vocab = w.vocab or 152064
+    sigma = w.logit_sigma or 3.0
+    lp = I.build_logprob_inputs(w.num_seqs, vocab, sigma, w.seed, device=dev)
+    nws = B.marl_logprobs_workspace_bytes(w.num_seqs, vocab)
+    lp_ws = B.alloc_workspace(nws, dev) if nws else None
+    lp_out = torch.empty(w.num_seqs, dtype=torch.float32, device=dev)
+
+    def step():
+        B.run_attn(attn, call)
+        B.marl_token_logprobs(lp.logits, lp.tokens, lp.temperature, lp_out, lp_ws)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.marl_profile_begin(a.steps)
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stage_ms, n_attn, n_lp = B.marl_profile_end()
+    assert n_attn == a.steps and n_lp == a.steps
+    assert B.marl_attn_read_flags(call.workspace) == 0
+    assert torch.isfinite(lp_out).all().item() and torch.isfinite(call.out.float()).all().item()
+
+    ms_per_step = dt / a.steps * 1e3
+    ptok, stok = attn.unique_kv_tokens()
+    bpt = attn.kv_bytes_per_token()
+    attn_ms = stage_ms["plan"] + stage_ms["prefix"] + stage_ms["suffix"] + stage_ms["merge"]
+    lp_ms = stage_ms["logprob"] + stage_ms["logprob_finish"]
+    suffix_gbps = stok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
+    res = {
+        "metric": "rollout decode step throughput (paged shared-prefix decode attention + token log-probs)",
+        "value": w.num_seqs / (ms_per_step * 1e-3),
+        "unit": "sequences*steps/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.num_seqs} seqs, {w.num_groups} prompts, Hq {w.Hq}/Hkv {w.Hkv}, "
+                               f"d 128, page 16, vocab {vocab}",
+                   "unique_kv_bytes": (ptok + stok) * bpt, "prefix_tokens": ptok, "suffix_tokens": stok,
+                   "suffix_chunk_tokens": call.layout.suffix_chunk_tokens,
+                   "prefix_chunk_tokens": call.layout.prefix_chunk_tokens},
+        "stage_ms": stage_ms,
+        "attn_unique_kv_GBps": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9,
+        "attn_pct_of_hbm_peak": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS * 100,
+        "attn_seq_steps_per_s": w.num_seqs / (attn_ms * 1e-3),
+        "logprob_rows_per_s": w.num_seqs / (lp_ms * 1e-3),
+        "logprob_GBps": w.num_seqs * vocab * 2 / (lp_ms * 1e-3) / 1e9,
+        "roofline": {"kernel": "suffix_kernel", "bound": "hbm", "achieved": suffix_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=4, lp_rows=256)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
