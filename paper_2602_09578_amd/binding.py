@@ -52,11 +52,12 @@ def load_library(build_if_missing: bool = True):
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        if not build_if_missing:
-            raise FileNotFoundError(LIB_PATH)
+    path = os.environ.get("MARL_DECODE_LIB", LIB_PATH)   # an explicitly chosen build, if any
+    if not os.path.exists(path):
+        if not build_if_missing or path != LIB_PATH:
+            raise FileNotFoundError(path)
         build_library()
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     PS, PL = ctypes.POINTER(AttnShape), ctypes.POINTER(PlanLayout)
     lib.marl_version.restype = ctypes.c_int
     lib.marl_status_string.restype = ctypes.c_char_p

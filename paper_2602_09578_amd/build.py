@@ -18,10 +18,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-I" + os.path.join(_ROOT, "include"), "-I" + CSRC]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
+def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH) -> str:
     """Compiles every source (always, also when a built library exists) and links."""
     os.makedirs(LIB_DIR, exist_ok=True)
-    objdir = os.path.join(LIB_DIR, "_build")
+    objdir = os.path.join(LIB_DIR, "_build", os.path.basename(out_path))
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):
@@ -37,11 +37,11 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out_path, *objs]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

@@ -20,6 +20,8 @@
 // K and V go straight from global memory into MFMA operand registers (16-byte loads; per
 // instruction a wave reads 16 x 64 B of K or 2 x 512 B of V); LDS is only used to combine
 // the four waves of a workgroup, which split the item's tokens between them.
+#include <type_traits>
+
 #include "marl_internal.h"
 
 namespace marl {
@@ -42,6 +44,25 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 
 constexpr int kWaves = kAttnThreads / 64;
 
+// Wave-uniform read of read-only input through the scalar cache.
+__device__ __forceinline__ int ld_uniform(const int32_t* p) {
+  return *reinterpret_cast<const int32_t __attribute__((address_space(4)))*>(
+      reinterpret_cast<uintptr_t>(p));
+}
+
+// 16-byte load of KV data, which is read once: the non-temporal hint keeps it from
+// displacing reusable lines (block tables, queries, partials) in the caches.
+#ifndef MARL_NT_LOADS
+#define MARL_NT_LOADS 1
+#endif
+__device__ __forceinline__ u32x4 ld_stream(const char* p) {
+#if MARL_NT_LOADS
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+#else
+  return *reinterpret_cast<const u32x4*>(p);
+#endif
+}
+
 // LDS per workgroup: (max, sum) of every wave and one buffer for a wave's accumulators.
 template <int MT>
 struct ItemLds {
@@ -62,7 +83,8 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = lane & 15, j = lane >> 4;
-  const float sc = fabsf(a.scale) * 1.44269504088896340736f;   // scores are kept in log2 units
+  // scores are kept in log2 units; a zero scale becomes a tiny one so that -inf * sc stays -inf
+  const float sc = fmaxf(fabsf(a.scale) * 1.44269504088896340736f, 1e-30f);
   const uint32_t sign_flip = a.scale < 0.f ? 0x80008000u : 0u;
   const int nslot = a.NCp + a.NCs;
 
@@ -97,80 +119,116 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
   const char* vbase = reinterpret_cast<const char*>(a.v_pages) + (size_t)kvh * (kPage * kD * 2) +
                       (i * (kPage * 2) + (j & 1) * 16);
 
-  for (int t0 = tok_begin + wave * kBlockTok; t0 < tok_end; t0 += kWaves * kBlockTok) {
-    int p0 = table_row[t0 >> 4];
-    int p1 = (t0 + kPage < tok_end) ? table_row[(t0 >> 4) + 1] : p0;
+  // Page ids of the 32-token step that starts at token t (wave-uniform, scalar loads).
+  auto load_pages = [&](int t, int& p0, int& p1) {
+    p0 = ld_uniform(table_row + (t >> 4));
+    p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
     if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
     if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
+  };
+  u32x4 kr[2][4], vr[8];
+  auto issue_k = [&](int p0, int p1) {
     const char* kp = kbase + (size_t)(i < 8 ? p0 : p1) * page_bytes;
-    const char* vp = vbase + (size_t)(j < 2 ? p0 : p1) * page_bytes;
-
-    u32x4 kr[2][4], vr[8];
 #pragma unroll
     for (int T = 0; T < 2; ++T)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kr[T][kk] = *reinterpret_cast<const u32x4*>(kp + T * (4 * kD * 2) + kk * 64);
+        kr[T][kk] = ld_stream(kp + T * (4 * kD * 2) + kk * 64);
+  };
+  auto issue_v = [&](int p0, int p1) {
+    const char* vp = vbase + (size_t)(j < 2 ? p0 : p1) * page_bytes;
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct) vr[ct] = *reinterpret_cast<const u32x4*>(vp + ct * (16 * kPage * 2));
+    for (int ct = 0; ct < 8; ++ct) vr[ct] = ld_stream(vp + ct * (16 * kPage * 2));
+  };
 
-    const bool ragged = t0 + kBlockTok > tok_end;   // wave-uniform
-    if (ragged) {
-      // zero the value slots no token owns (they may hold anything, NaN included)
+  // Software pipeline: the K registers are refilled for the next step as soon as the score
+  // MFMAs have consumed them, the V registers as soon as the output MFMAs have; page ids are
+  // fetched one step ahead.  So a wave keeps 16 KB of loads in flight while it computes.
+  // The last step of a wave is peeled (no refill; it alone can be ragged) so that the loop
+  // body has no conditional loads and every wait leaves the younger 8 loads in flight.
+  int t0 = tok_begin + wave * kBlockTok;
+  int tn = t0 + kWaves * kBlockTok;
+  int n0 = 0, n1 = 0;
+
+  auto step = [&](auto has_next_tag) {
+    constexpr bool kHasNext = decltype(has_next_tag)::value;
+    f32x4 s[MT][2];
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const int tok = t0 + 8 * j + 2 * d;
-        const uint32_t mask = (tok < tok_end ? 0x0000ffffu : 0u) | (tok + 1 < tok_end ? 0xffff0000u : 0u);
+    for (int qt = 0; qt < MT; ++qt)
 #pragma unroll
-        for (int ct = 0; ct < 8; ++ct) vr[ct][d] &= mask;
+      for (int T = 0; T < 2; ++T) {
+        s[qt][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) s[qt][T] = mfma_16x16x32(kr[T][kk], qreg[qt][kk], s[qt][T]);
+      }
+    if constexpr (kHasNext) issue_k(n0, n1);
+
+    if constexpr (!kHasNext) {
+      if (t0 + kBlockTok > tok_end) {   // wave-uniform: the ragged end of a chunk
+        // tokens past the end: score -inf (weight 0), and zero their value slots, which may
+        // hold anything (NaN included)
+#pragma unroll
+        for (int qt = 0; qt < MT; ++qt)
+#pragma unroll
+          for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (t0 + 8 * j + 4 * T + e >= tok_end) s[qt][T][e] = -INFINITY;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const int tok = t0 + 8 * j + 2 * d;
+          const uint32_t mask = (tok < tok_end ? 0x0000ffffu : 0u) | (tok + 1 < tok_end ? 0xffff0000u : 0u);
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) vr[ct][d] &= mask;
+        }
       }
     }
 
+    u32x4 pb[MT];
 #pragma unroll
     for (int qt = 0; qt < MT; ++qt) {
-      f32x4 s[2];
-#pragma unroll
-      for (int T = 0; T < 2; ++T) {
-        s[T] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) s[T] = mfma_16x16x32(kr[T][kk], qreg[qt][kk], s[T]);
-      }
-      bool valid[2][4];
-#pragma unroll
-      for (int T = 0; T < 2; ++T)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          valid[T][e] = !ragged || (t0 + 8 * j + 4 * T + e < tok_end);
-          if (!valid[T][e]) s[T][e] = -INFINITY;
-        }
-      float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
-                       fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+      const f32x4 s0 = s[qt][0], s1 = s[qt][1];
+      float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                       fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float m_new = fmaxf(m_run[qt], mx * sc);
       const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-      float p[2][4];
-      float psum = 0.f;
+      float p[8];
 #pragma unroll
-      for (int T = 0; T < 2; ++T)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float v = __builtin_amdgcn_exp2f(__builtin_fmaf(s[T][e], sc, -m_new));
-          if (!valid[T][e]) v = 0.f;
-          p[T][e] = v;
-          psum += v;
-        }
+      for (int e = 0; e < 4; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], sc, -m_new));
+        p[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], sc, -m_new));
+      }
+      const float psum = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
       if (__builtin_amdgcn_ballot_w64(m_new > m_run[qt]) != 0) {   // wave-uniform
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= alpha;
       }
       l_run[qt] = l_run[qt] * alpha + psum;
       m_run[qt] = m_new;
-      const u32x4 pb = {pack_bf16(p[0][0], p[0][1]), pack_bf16(p[0][2], p[0][3]),
-                        pack_bf16(p[1][0], p[1][1]), pack_bf16(p[1][2], p[1][3])};
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = mfma_16x16x32(vr[ct], pb, acc[qt][ct]);
+      pb[qt] = u32x4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
     }
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+      for (int qt = 0; qt < MT; ++qt) acc[qt][ct] = mfma_16x16x32(vr[ct], pb[qt], acc[qt][ct]);
+
+    if constexpr (kHasNext) {
+      issue_v(n0, n1);
+      t0 = tn;
+      tn += kWaves * kBlockTok;
+      if (tn < tok_end) load_pages(tn, n0, n1);
+    }
+  };
+
+  if (t0 < tok_end) {
+    load_pages(t0, n0, n1);
+    issue_k(n0, n1);
+    issue_v(n0, n1);
+    if (tn < tok_end) load_pages(tn, n0, n1);
+    while (tn < tok_end) step(std::true_type{});
+    step(std::false_type{});
   }
 
   // the four lanes that share a q-row each hold a part of its sum
