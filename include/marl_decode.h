@@ -73,6 +73,7 @@ typedef struct marl_attn_plan_layout {
   size_t group_count_off;        /* int32[NG]   sequences per group */
   size_t group_start_off;        /* int32[NG+1] exclusive scan of group_count */
   size_t seq_rank_off;           /* int32[NS]   scratch */
+  size_t group_tmp_off;          /* int32[NS]   scratch */
   size_t group_seqs_off;         /* int32[NS]   sequence ids grouped by group (CSR values) */
   size_t suffix_items_off;       /* int32[max_suffix_items][4] {seq, tok_begin, tok_end, 0} */
   size_t prefix_items_off;       /* int32[max_prefix_items][4] {group, tok_begin, tok_end, row_begin} */

@@ -34,7 +34,7 @@ class PlanLayout(ctypes.Structure):
         "suffix_chunk_tokens", "prefix_chunk_tokens", "suffix_slots", "prefix_slots",
         "rows_per_qblock", "max_suffix_items", "max_prefix_items", "reserved")] + \
         [(n, SZ) for n in (
-            "counters_off", "group_count_off", "group_start_off", "seq_rank_off", "group_seqs_off",
+            "counters_off", "group_count_off", "group_start_off", "seq_rank_off", "group_tmp_off", "group_seqs_off",
             "suffix_items_off", "prefix_items_off", "partial_ml_off", "partial_o_off", "total_bytes")]
 
 

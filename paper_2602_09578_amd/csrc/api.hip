@@ -77,6 +77,7 @@ int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
   L->group_count_off = take((size_t)NG * 4);
   L->group_start_off = take((size_t)(NG + 1) * 4);
   L->seq_rank_off = take((size_t)NS * 4);
+  L->group_tmp_off = take((size_t)NS * 4);
   L->group_seqs_off = take((size_t)NS * 4);
   L->suffix_items_off = take((size_t)max_s_items * 16);
   L->prefix_items_off = take((size_t)max_p_items * 16);
@@ -142,6 +143,7 @@ int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArg
   a.group_count = reinterpret_cast<int32_t*>(w + L.group_count_off);
   a.group_start = reinterpret_cast<int32_t*>(w + L.group_start_off);
   a.seq_rank = reinterpret_cast<int32_t*>(w + L.seq_rank_off);
+  a.group_tmp = reinterpret_cast<int32_t*>(w + L.group_tmp_off);
   a.group_seqs = reinterpret_cast<int32_t*>(w + L.group_seqs_off);
   a.suffix_items = reinterpret_cast<int4*>(w + L.suffix_items_off);
   a.prefix_items = reinterpret_cast<int4*>(w + L.prefix_items_off);

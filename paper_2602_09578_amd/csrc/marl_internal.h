@@ -29,6 +29,7 @@ struct AttnArgs {
   int32_t* group_count;
   int32_t* group_start;
   int32_t* seq_rank;
+  int32_t* group_tmp;
   int32_t* group_seqs;
   int4* suffix_items;
   int4* prefix_items;

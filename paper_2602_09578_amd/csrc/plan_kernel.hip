@@ -118,8 +118,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   const int n_prefix_items = block_exclusive_scan<false>(hist_p, hist_p, ncls_p, tmp);
 
   for (int s = tid; s < a.NS; s += kPlanThreads) {
+    // members of a group in arrival order first; put into ascending order further down
     const int rank = a.seq_rank[s];
-    if (rank >= 0) a.group_seqs[ld_agent(a.group_start + a.group_of_seq[s]) + rank] = s;
+    if (rank >= 0) a.group_tmp[ld_agent(a.group_start + a.group_of_seq[s]) + rank] = s;
     int dummy = 0;
     const int S = clamp_len(a.suffix_lens[s], max_st, dummy);
     const int nfull = S / Cs, tail = S % Cs;
@@ -154,20 +155,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   __threadfence();
   __syncthreads();
 
-  // make the CSR order deterministic: ascending sequence id inside every small group
-  for (int g = tid; g < a.NG; g += kPlanThreads) {
+  // make the CSR order deterministic: inside every group of at most 64 sequences a member's
+  // final place is the number of members with a smaller id (larger groups keep arrival
+  // order; the order of rows never changes a result)
+  for (int s = tid; s < a.NS; s += kPlanThreads) {
+    const int rank = a.seq_rank[s];
+    if (rank < 0) continue;
+    const int g = a.group_of_seq[s];
     const int b = ld_agent(a.group_start + g), n = ld_agent(a.group_count + g);
+    int place = rank;
     if (n <= 64) {
-      for (int i = 1; i < n; ++i) {
-        const int v = ld_agent(a.group_seqs + b + i);
-        int k = i - 1;
-        while (k >= 0 && ld_agent(a.group_seqs + b + k) > v) {
-          a.group_seqs[b + k + 1] = ld_agent(a.group_seqs + b + k);
-          --k;
-        }
-        a.group_seqs[b + k + 1] = v;
+      place = 0;
+      for (int k0 = 0; k0 < n; k0 += 8) {
+        int v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (k0 + u < n) ? ld_agent(a.group_tmp + b + k0 + u) : 0x7fffffff;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) place += v[u] < s;
       }
     }
+    a.group_seqs[b + place] = s;
   }
   if (flags) atomicOr(&a.counters[MARL_CTR_FLAGS], flags);
   if (tid == 0) {
