@@ -65,7 +65,7 @@ typedef struct marl_attn_plan_layout {
   int32_t prefix_chunk_tokens;   /* Cp actually used */
   int32_t suffix_slots;          /* NCs = max(1, ceil(max_suffix_pages*16 / Cs)) */
   int32_t prefix_slots;          /* NCp = max(1, ceil(max_prefix_pages*16 / Cp)) */
-  int32_t rows_per_qblock;       /* query rows one prefix work item covers (64) */
+  int32_t rows_per_qblock;       /* query rows one prefix work item covers (128) */
   int32_t max_suffix_items;      /* NS * NCs */
   int32_t max_prefix_items;      /* (NG + NS*(Hq/Hkv)/rows_per_qblock + 1) * NCp */
   int32_t reserved;

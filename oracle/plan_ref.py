@@ -15,7 +15,7 @@ from typing import List, Tuple
 import numpy as np
 
 PAGE = 16
-ROWS_PER_QBLOCK = 64
+ROWS_PER_QBLOCK = 128
 
 
 def _ceil_div(a: int, b: int) -> int:

@@ -17,9 +17,11 @@
 //   output:  D[channel][q-row] += V^T-tile (A operand) x P^T (B operand), 8 channel tiles.
 //            V pages are stored [channel][slot], so lane (i, j) loads its 8 tokens of
 //            channel 16*ct + i with one 16-byte load.
-// K and V go straight from global memory into MFMA operand registers (16-byte loads; per
-// instruction a wave reads 16 x 64 B of K or 2 x 512 B of V); LDS is only used to combine
+// Suffix kernel: K and V go straight from global memory into MFMA operand registers (16-byte
+// loads; per instruction a wave reads 16 x 64 B of K or 2 x 512 B of V); LDS only combines
 // the four waves of a workgroup, which split the item's tokens between them.
+// Prefix kernel: the four waves split the query rows instead and share each K/V step
+// through a double-buffered LDS tile (described at the kernel).
 #include <type_traits>
 
 #include "marl_internal.h"
@@ -325,30 +327,234 @@ __global__ __launch_bounds__(kAttnThreads) void suffix_kernel(AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Prefix kernel: one work item = (group, chunk of prefix tokens, block of up to 64 query
+// Prefix kernel: one work item = (group, chunk of prefix tokens, block of up to 128 query
 // rows, KV head).  Query row rho of a group is (its rho / R -th sequence, head kvh*R + rho % R).
+//
+// Here the four waves split the QUERY rows (16-row tile t belongs to wave t % 4) and every
+// wave sees all tokens, so the group's K/V must reach all four: each 32-token step (two
+// pages, 16 KB of K and V) is fetched once by the workgroup with fully coalesced 16-byte
+// loads (a wave reads 1 KB contiguous per instruction), staged in registers, written to a
+// double-buffered LDS tile and read back in MFMA operand layout.  Loads run two steps
+// ahead (32 KB in flight per workgroup).  No cross-wave reduction is needed.
+//
+// LDS tile of one step (16 KB): K as 32 token rows of 256 B, the 16-byte chunk index of
+// row tau XOR-ed with (tau&3)|((tau>>1)&4) so that the 8 lanes of an operand read hit 8
+// different 16-byte bank groups; V as [page][channel][2 halves of 8 slots], the 16-byte
+// unit index u XOR-ed with (u>>3)&1 for the same reason.
 // ---------------------------------------------------------------------------------------
-template <int MT>
+constexpr int kStepBytes = 2 * kBlockTok * kD * 2;   // K + V of one 32-token step
+struct PrefixLds {
+  __attribute__((aligned(16))) char buf[2][kStepBytes];
+};
+
+template <int MTW>
 __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, const int kvh,
-                                            ItemLds<4>& lds, int& bad_page) {
-  const int g = it.x;
+                                            PrefixLds& lds, int& bad_page) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i = lane & 15, j = lane >> 4;
+  const int g = it.x, tok_begin = it.y, tok_end = it.z, row_begin = it.w;
   const int gstart = a.group_start[g];
   const int nrows = a.group_count[g] * a.R;
-  const int i = threadIdx.x & 15;
-  int row_index[MT];
+  const int32_t* table_row = a.prefix_table + (size_t)g * a.max_pp;
+  const float sc = fmaxf(fabsf(a.scale) * 1.44269504088896340736f, 1e-30f);
+  const uint32_t sign_flip = a.scale < 0.f ? 0x80008000u : 0u;
+  const int nslot = a.NCp + a.NCs;
+  const int slot = tok_begin / a.Cp;
+
+  // this wave's tiles: wave, wave + 4, ...; nt of them hold at least one real row
+  const int tiles_total = (min(kRowsPerQBlock, nrows - row_begin) + 15) >> 4;
+  const int nt = max(0, min(MTW, (tiles_total - wave + kWaves - 1) / kWaves));   // wave-uniform
+  int row_index[MTW];
+  u32x4 qreg[MTW][4];
 #pragma unroll
-  for (int qt = 0; qt < MT; ++qt) {
-    const int rho = it.w + qt * 16 + i;
+  for (int qt = 0; qt < MTW; ++qt) {
+    const int rho = row_begin + (qt * kWaves + wave) * 16 + i;
     int idx = -1;
-    if (rho < nrows) idx = a.group_seqs[gstart + rho / a.R] * a.Hq + kvh * a.R + rho % a.R;
+    if (rho < nrows && (qt * kWaves + wave) * 16 < kRowsPerQBlock)
+      idx = a.group_seqs[gstart + rho / a.R] * a.Hq + kvh * a.R + rho % a.R;
     row_index[qt] = idx;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (idx >= 0) {
+        v = *reinterpret_cast<const u32x4*>(a.q + (size_t)idx * kD + (4 * kk + j) * 8);
+        v ^= sign_flip;
+      }
+      qreg[qt][kk] = v;
+    }
   }
-  process_item<MT>(a, a.prefix_table + (size_t)g * a.max_pp, it.y, it.z, kvh, row_index,
-                   it.y / a.Cp, reinterpret_cast<ItemLds<MT>&>(lds), bad_page);
+  f32x4 acc[MTW][8];
+  float m_run[MTW], l_run[MTW];
+#pragma unroll
+  for (int qt = 0; qt < MTW; ++qt) {
+    m_run[qt] = -INFINITY;
+    l_run[qt] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int nsteps = (tok_end - tok_begin + kBlockTok - 1) / kBlockTok;
+  const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
+  const char* kbase = reinterpret_cast<const char*>(a.k_pages) + (size_t)kvh * (kPage * kD * 2) + tid * 16;
+  const char* vbase = reinterpret_cast<const char*>(a.v_pages) + (size_t)kvh * (kPage * kD * 2) + tid * 16;
+  const char* dummy = reinterpret_cast<const char*>(a.q);   // any valid 16 bytes
+
+  // Page ids of step n (wave-uniform scalar loads); steps past the end yield -1.
+  auto load_ids = [&](int n, int& p0, int& p1) {
+    p0 = -1;
+    p1 = -1;
+    if (n < nsteps) {
+      const int t = tok_begin + n * kBlockTok;
+      p0 = ld_uniform(table_row + (t >> 4));
+      p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
+      if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
+      if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
+    }
+  };
+  // The loads are unconditional (a step past the end re-reads 16 valid bytes that are never
+  // used) so that every wait in the loop knows exactly how many younger loads are in flight.
+  auto issue = [&](int p0, int p1, u32x4 (&st)[4]) {
+    const bool ok = p0 >= 0;
+    st[0] = ld_stream(ok ? kbase + (size_t)p0 * page_bytes : dummy);
+    st[1] = ld_stream(ok ? kbase + (size_t)p1 * page_bytes : dummy);
+    st[2] = ld_stream(ok ? vbase + (size_t)p0 * page_bytes : dummy);
+    st[3] = ld_stream(ok ? vbase + (size_t)p1 * page_bytes : dummy);
+  };
+  // thread tid holds, of each page, slot tid/16, chunk tid%16 of K and 16-byte unit tid of V
+  const int k_wr = (tid >> 4) * 256 + (((tid & 15) ^ ((tid >> 4) & 3) ^ (((tid >> 4) >> 1) & 4)) << 4);
+  const int v_wr = 2 * kBlockTok * kD + ((tid ^ ((tid >> 3) & 1)) << 4);
+  auto stage_to_lds = [&](const u32x4 (&st)[4], char* buf) {
+    // K rows of page 1 are tau = 16 + slot: (tau&3)|((tau>>1)&4) is the same as for page 0
+    *reinterpret_cast<u32x4*>(buf + k_wr) = st[0];
+    *reinterpret_cast<u32x4*>(buf + 16 * 256 + k_wr) = st[1];
+    *reinterpret_cast<u32x4*>(buf + v_wr) = st[2];
+    *reinterpret_cast<u32x4*>(buf + 4096 + v_wr) = st[3];
+  };
+  // operand reads: K row tau = 8*(i/4) + 4T + i%4, whose swizzle key is i & 7
+  const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
+  const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
+
+  auto compute = [&](int n, const char* buf) {
+    const int t0 = tok_begin + n * kBlockTok;
+    const bool ragged = t0 + kBlockTok > tok_end;   // wave-uniform; only the chunk's last step
+    u32x4 pb[MTW];
+    {
+      u32x4 kr[2][4];
+#pragma unroll
+      for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ (i & 7)) << 4));
+#pragma unroll
+      for (int qt = 0; qt < MTW; ++qt) {
+        pb[qt] = u32x4{0u, 0u, 0u, 0u};
+        if (qt < nt) {   // wave-uniform
+          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            s0 = mfma_16x16x32(kr[0][kk], qreg[qt][kk], s0);
+            s1 = mfma_16x16x32(kr[1][kk], qreg[qt][kk], s1);
+          }
+          if (ragged) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (t0 + 8 * j + e >= tok_end) s0[e] = -INFINITY;
+              if (t0 + 8 * j + 4 + e >= tok_end) s1[e] = -INFINITY;
+            }
+          }
+          float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                           fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run[qt], mx * sc);
+          const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+          float p[8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], sc, -m_new));
+            p[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], sc, -m_new));
+          }
+          const float psum = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+          if (__builtin_amdgcn_ballot_w64(m_new > m_run[qt]) != 0) {   // wave-uniform
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= alpha;
+          }
+          l_run[qt] = l_run[qt] * alpha + psum;
+          m_run[qt] = m_new;
+          pb[qt] = u32x4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+        }
+      }
+    }
+    u32x4 vr[8];
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) {
+      const int u = 2 * (16 * ct + i) + (j & 1);
+      vr[ct] = *reinterpret_cast<const u32x4*>(buf + v_rd + ((u ^ ((i >> 2) & 1)) << 4));
+    }
+    if (ragged) {
+      // value slots no token owns may hold anything (NaN included): zero them
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const int tok = t0 + 8 * j + 2 * d;
+        const uint32_t mask = (tok < tok_end ? 0x0000ffffu : 0u) | (tok + 1 < tok_end ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) vr[ct][d] &= mask;
+      }
+    }
+#pragma unroll
+    for (int qt = 0; qt < MTW; ++qt)
+      if (qt < nt) {
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = mfma_16x16x32(vr[ct], pb[qt], acc[qt][ct]);
+      }
+  };
+
+  u32x4 stA[4], stB[4];
+  int p0, p1;
+  load_ids(0, p0, p1);
+  issue(p0, p1, stA);
+  load_ids(1, p0, p1);
+  issue(p0, p1, stB);
+  load_ids(2, p0, p1);
+  stage_to_lds(stA, lds.buf[0]);
+  __syncthreads();
+  for (int n = 0; n < nsteps; n += 2) {
+    // even step: refill A (two steps ahead), compute from buffer 0, hand B to buffer 1
+    issue(p0, p1, stA);
+    load_ids(n + 3, p0, p1);
+    compute(n, lds.buf[0]);
+    stage_to_lds(stB, lds.buf[1]);
+    __syncthreads();
+    if (n + 1 < nsteps) {
+      issue(p0, p1, stB);
+      load_ids(n + 4, p0, p1);
+      compute(n + 1, lds.buf[1]);
+      stage_to_lds(stA, lds.buf[0]);
+      __syncthreads();
+    }
+  }
+  // a workgroup-wide barrier has been passed since the last LDS read: the next item may
+  // overwrite the buffers
+
+#pragma unroll
+  for (int qt = 0; qt < MTW; ++qt) {
+    float l = l_run[qt];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (row_index[qt] >= 0) {
+      const size_t ps = (size_t)row_index[qt] * nslot + slot;
+      float* dst = a.partial_o + ps * kD + 4 * j;
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct];
+      if (j == 0) a.partial_ml[ps] = make_float2(m_run[qt], l);
+    }
+  }
 }
 
-__global__ __launch_bounds__(kAttnThreads) void prefix_kernel(AttnArgs a) {
-  __shared__ ItemLds<4> lds;
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefix_kernel(AttnArgs a) {
+  __shared__ PrefixLds lds;
   __shared__ int next_item;
   const int n_work = a.counters[MARL_CTR_NUM_PREFIX_ITEMS] * a.Hkv;
   int bad_page = 0;
@@ -361,11 +567,8 @@ __global__ __launch_bounds__(kAttnThreads) void prefix_kernel(AttnArgs a) {
     const int4 it = a.prefix_items[qi / a.Hkv];
     const int kvh = qi % a.Hkv;
     const int rows = min(kRowsPerQBlock, a.group_count[it.x] * a.R - it.w);
-    const int mt = (rows + 15) >> 4;   // workgroup-uniform
-    if (mt <= 1) prefix_item<1>(a, it, kvh, lds, bad_page);
-    else if (mt == 2) prefix_item<2>(a, it, kvh, lds, bad_page);
-    else if (mt == 3) prefix_item<3>(a, it, kvh, lds, bad_page);
-    else prefix_item<4>(a, it, kvh, lds, bad_page);
+    if (rows <= 16 * kWaves) prefix_item<1>(a, it, kvh, lds, bad_page);   // workgroup-uniform
+    else prefix_item<2>(a, it, kvh, lds, bad_page);
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }

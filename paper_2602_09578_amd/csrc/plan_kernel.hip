@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   const int nseq_grouped = block_exclusive_scan<true>(a.group_count, a.group_start, a.NG, tmp);
   if (tid == 0) a.group_start[a.NG] = nseq_grouped;
 
-  // groups: histogram of prefix items (one per chunk and per block of 64 query rows)
+  // groups: histogram of prefix items (one per chunk and per block of query rows)
   for (int g = tid; g < a.NG; g += kPlanThreads) {
     const int P = clamp_len(a.prefix_lens[g], max_pt, flags);
     const int nqb = (ld_agent(a.group_count + g) * R + kRowsPerQBlock - 1) / kRowsPerQBlock;

@@ -44,7 +44,7 @@ def status_of(fn):
 def test_layout_and_default_chunks():
     L = B.marl_attn_plan_layout_for(good_shape())
     assert (L.suffix_chunk_tokens, L.prefix_chunk_tokens) == (256, 256)
-    assert (L.suffix_slots, L.prefix_slots, L.rows_per_qblock) == (1, 1, 64)
+    assert (L.suffix_slots, L.prefix_slots, L.rows_per_qblock) == (1, 1, 128)
     assert L.total_bytes == B.marl_workspace_bytes(good_shape())
     offs = [L.counters_off, L.group_count_off, L.group_start_off, L.seq_rank_off, L.group_tmp_off, L.group_seqs_off,
             L.suffix_items_off, L.prefix_items_off, L.partial_ml_off, L.partial_o_off, L.total_bytes]
