@@ -83,13 +83,21 @@ def main():
 
     for _ in range(a.warmup):
         step()
+    # timed region 1: exactly K steps, nothing else on the stream -> `value`
     torch.cuda.synchronize()
-    B.marl_profile_begin(a.steps)
     t0 = time.perf_counter()
     for _ in range(a.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # timed region 2: the same K steps with the library recording HIP events around every
+    # kernel on the call's stream -> per-kernel durations (the events cost a few us per kernel)
+    B.marl_profile_begin(a.steps)
+    t1 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_prof = time.perf_counter() - t1
     stage_ms, n_attn, n_lp = B.marl_profile_end()
     assert n_attn == a.steps and n_lp == a.steps
     assert B.marl_attn_read_flags(call.workspace) == 0
@@ -114,6 +122,7 @@ def main():
                    "suffix_chunk_tokens": call.layout.suffix_chunk_tokens,
                    "prefix_chunk_tokens": call.layout.prefix_chunk_tokens},
         "stage_ms": stage_ms,
+        "ms_per_step_with_stage_events": dt_prof / a.steps * 1e3,
         "attn_unique_kv_GBps": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9,
         "attn_pct_of_hbm_peak": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS * 100,
         "attn_seq_steps_per_s": w.num_seqs / (attn_ms * 1e-3),

@@ -87,7 +87,9 @@ enum {
   MARL_CTR_NUM_PREFIX_ITEMS = 1,
   MARL_CTR_SUFFIX_CURSOR = 2,    /* work-queue cursors, zero after the plan kernel */
   MARL_CTR_PREFIX_CURSOR = 3,
-  MARL_CTR_FLAGS = 4             /* MARL_FLAG_* bits set by the kernels */
+  MARL_CTR_FLAGS = 4,            /* MARL_FLAG_* bits set by the kernels */
+  MARL_CTR_NUM_LONG_SUFFIX_ITEMS = 5, /* suffix items of more than 128 tokens: they head the list */
+  MARL_CTR_SHORT_CURSOR = 6      /* work-queue cursor of the remaining (short) suffix items */
 };
 enum {
   MARL_FLAG_BAD_GROUP = 1,       /* a group_of_seq entry was outside [0, NG) */
@@ -133,7 +135,8 @@ int marl_workspace_bytes(const marl_attn_shape* shape, size_t* bytes);
  * Work: a plan kernel builds the group->sequences CSR and two work lists (prefix items per
  * group, suffix items per sequence, each at most a chunk of tokens, longest first); a
  * prefix kernel streams each group's prefix KV once for all of the group's query rows; a
- * suffix kernel streams each sequence's own KV; a merge kernel combines the per-chunk
+ * suffix kernel streams each sequence's own KV (items of at most 128 tokens are taken, one per
+ * wave, by the prefix kernel's workgroups before they start on the prefix items); a merge kernel combines the per-chunk
  * (max, sum, output) partials in a fixed order, so results are bit-identical across runs.
  */
 int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t workspace_bytes,

@@ -16,6 +16,7 @@ import numpy as np
 
 PAGE = 16
 ROWS_PER_QBLOCK = 128
+SHORT_TOKENS = 128     # suffix items above this many tokens head the list
 
 
 def _ceil_div(a: int, b: int) -> int:
@@ -50,6 +51,10 @@ class PlanRef:
     suffix_items: List[Tuple[int, int, int, int]]   # (seq, tok_begin, tok_end, 0)
     prefix_items: List[Tuple[int, int, int, int]]   # (group, tok_begin, tok_end, row_begin)
     flags: int
+
+    @property
+    def num_long_suffix_items(self) -> int:
+        return sum(1 for it in self.suffix_items if it[2] - it[1] > SHORT_TOKENS)
 
 
 def build_plan(prefix_lens, suffix_lens, group_of_seq, Hq: int, Hkv: int, max_prefix_pages: int,

@@ -18,7 +18,8 @@ VP = ctypes.c_void_p
 
 MARL_OUT_BF16, MARL_OUT_F32 = 0, 1
 STAGES = ("plan", "prefix", "suffix", "merge", "logprob", "logprob_finish")
-CTR_NUM_SUFFIX_ITEMS, CTR_NUM_PREFIX_ITEMS, CTR_SUFFIX_CURSOR, CTR_PREFIX_CURSOR, CTR_FLAGS = range(5)
+CTR_NUM_SUFFIX_ITEMS, CTR_NUM_PREFIX_ITEMS, CTR_SUFFIX_CURSOR, CTR_PREFIX_CURSOR, CTR_FLAGS, \
+    CTR_NUM_LONG_SUFFIX_ITEMS, CTR_SHORT_CURSOR = range(7)
 FLAG_BAD_GROUP, FLAG_LEN_CLAMPED, FLAG_BAD_PAGE = 1, 2, 4
 
 

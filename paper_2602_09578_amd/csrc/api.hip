@@ -250,7 +250,7 @@ int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t works
   hipError_t e;
   if ((e = T.run(MARL_STAGE_PLAN, [&] { return marl::launch_plan(a, st); })) != hipSuccess)
     return hip_fail(e, "plan kernel");
-  if (a.NG > 0 && a.max_pp > 0) {
+  {  // always launched: its workgroups also process the short suffix items
     if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * g_prefix_bpc, st); })) != hipSuccess)
       return hip_fail(e, "prefix kernel");
   }

@@ -74,16 +74,19 @@ struct ItemLds {
 };
 
 // Processes tokens [tok_begin, tok_end) of one block-table row for MT tiles of query rows
-// and writes one partial per valid row.  Called by all four waves of the workgroup.
+// and writes one partial per valid row.  NW is the number of waves that share the item:
+//   NW = 4: called by all four waves of the workgroup, which take the 32-token steps in
+//           turn and are combined through LDS (workgroup barriers inside);
+//   NW = 1: called by one wave on its own (no LDS, no barrier): for short items.
 //   row_index[qt]: for this lane's q-row (i) of tile qt, seq*Hq + head, or -1 if the row
 //   does not exist.  slot: partial slot of this chunk.
-template <int MT>
+template <int MT, int NW>
 __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* __restrict__ table_row,
                                              const int tok_begin, const int tok_end, const int kvh,
                                              const int (&row_index)[MT], const int slot,
                                              ItemLds<MT>& lds, int& bad_page) {
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wave = NW == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = lane & 15, j = lane >> 4;
   // scores are kept in log2 units; a zero scale becomes a tiny one so that -inf * sc stays -inf
   const float sc = fmaxf(fabsf(a.scale) * 1.44269504088896340736f, 1e-30f);
@@ -148,8 +151,9 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
   // fetched one step ahead.  So a wave keeps 16 KB of loads in flight while it computes.
   // The last step of a wave is peeled (no refill; it alone can be ragged) so that the loop
   // body has no conditional loads and every wait leaves the younger 8 loads in flight.
+  constexpr int stride = NW * kBlockTok;
   int t0 = tok_begin + wave * kBlockTok;
-  int tn = t0 + kWaves * kBlockTok;
+  int tn = t0 + stride;
   int n0 = 0, n1 = 0;
 
   auto step = [&](auto has_next_tag) {
@@ -219,7 +223,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
     if constexpr (kHasNext) {
       issue_v(n0, n1);
       t0 = tn;
-      tn += kWaves * kBlockTok;
+      tn += stride;
       if (tn < tok_end) load_pages(tn, n0, n1);
     }
   };
@@ -240,53 +244,60 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
     l_run[qt] += __shfl_xor(l_run[qt], 32);
   }
 
-  // combine the waves in a fixed order: every wave rescales to the common max, then waves
-  // 1..3 hand their accumulators to wave 0 one after the other
-  if (j == 0) {
-#pragma unroll
-    for (int qt = 0; qt < MT; ++qt) {
-      lds.m[wave][qt * 16 + i] = m_run[qt];
-      lds.l[wave][qt * 16 + i] = l_run[qt];
-    }
-  }
-  __syncthreads();
   float m_all[MT], l_all[MT];
 #pragma unroll
   for (int qt = 0; qt < MT; ++qt) {
-    float mm = lds.m[0][qt * 16 + i];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, lds.m[w][qt * 16 + i]);
-    float ll = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float mw = lds.m[w][qt * 16 + i];
-      const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
-      ll += lds.l[w][qt * 16 + i] * f;
-    }
-    m_all[qt] = mm;
-    l_all[qt] = ll;
-    const float f_own = (m_run[qt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[qt] - mm);
-#pragma unroll
-    for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= f_own;
+    m_all[qt] = m_run[qt];
+    l_all[qt] = l_run[qt];
   }
-  for (int w = 1; w < kWaves; ++w) {
-    if (wave == w) {
+  if constexpr (NW > 1) {
+    // combine the waves in a fixed order: every wave rescales to the common max, then waves
+    // 1..3 hand their accumulators to wave 0 one after the other
+    if (j == 0) {
 #pragma unroll
-      for (int qt = 0; qt < MT; ++qt)
-#pragma unroll
-        for (int ct = 0; ct < 8; ++ct) lds.acc[(qt * 8 + ct) * 64 + lane] = acc[qt][ct];
+      for (int qt = 0; qt < MT; ++qt) {
+        lds.m[wave][qt * 16 + i] = m_run[qt];
+        lds.l[wave][qt * 16 + i] = l_run[qt];
+      }
     }
     __syncthreads();
-    if (wave == 0) {
 #pragma unroll
-      for (int qt = 0; qt < MT; ++qt)
+    for (int qt = 0; qt < MT; ++qt) {
+      float mm = lds.m[0][qt * 16 + i];
 #pragma unroll
-        for (int ct = 0; ct < 8; ++ct) acc[qt][ct] += lds.acc[(qt * 8 + ct) * 64 + lane];
+      for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, lds.m[w][qt * 16 + i]);
+      float ll = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float mw = lds.m[w][qt * 16 + i];
+        const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
+        ll += lds.l[w][qt * 16 + i] * f;
+      }
+      m_all[qt] = mm;
+      l_all[qt] = ll;
+      const float f_own = (m_run[qt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[qt] - mm);
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= f_own;
     }
-    __syncthreads();
+    for (int w = 1; w < kWaves; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int qt = 0; qt < MT; ++qt)
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) lds.acc[(qt * 8 + ct) * 64 + lane] = acc[qt][ct];
+      }
+      __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int qt = 0; qt < MT; ++qt)
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) acc[qt][ct] += lds.acc[(qt * 8 + ct) * 64 + lane];
+      }
+      __syncthreads();
+    }
   }
 
-  if (wave == 0) {
+  if (wave == 0) {   // with NW = 1 every wave is its own "wave 0"
 #pragma unroll
     for (int qt = 0; qt < MT; ++qt) {
       if (row_index[qt] >= 0) {
@@ -301,13 +312,28 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
 }
 
 // ---------------------------------------------------------------------------------------
-// Suffix kernel: one work item = (sequence, chunk of its generated tokens, KV head); the
+// Suffix kernels: one work item = (sequence, chunk of its generated tokens, KV head); the
 // R = Hq/Hkv query heads of that KV head are the (zero-padded) 16-row tile.
+//
+// The item list is sorted longest first, so it splits into a head of long items (more than
+// kShortTokens tokens) and a tail of short ones.
+//   suffix_kernel:       long items, one per workgroup (waves take the 32-token steps in
+//                        turn), taken from the queue only when the workgroup is free
+//                        (reserving an item early would undo the longest-first balancing).
+//   short_suffix_items:  short items, one per wave, four queue entries per round, with no
+//                        LDS traffic or barrier inside an item, so a batch of tiny sequences
+//                        does not pay a workgroup's fixed costs per sequence; the next
+//                        round's indices and records are fetched while the current one runs.
+//                        It runs as the first phase of the PREFIX kernel's workgroups: as a
+//                        phase of the suffix kernel it slowed the long items' hot loop down
+//                        by a few percent (shared register allocation), as a kernel of its
+//                        own it cost one more launch per call, and at the end of any kernel
+//                        its latency-bound rounds stretch the tail.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kAttnThreads) void suffix_kernel(AttnArgs a) {
   __shared__ ItemLds<1> lds;
   __shared__ int next_item;
-  const int n_work = a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] * a.Hkv;
+  const int n_work = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
   int bad_page = 0;
   for (;;) {
     if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_SUFFIX_CURSOR], 1);
@@ -320,10 +346,58 @@ __global__ __launch_bounds__(kAttnThreads) void suffix_kernel(AttnArgs a) {
     const int s = it.x;
     const int i = threadIdx.x & 15;
     const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
-    process_item<1>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
-                    a.NCp + it.y / a.Cs, lds, bad_page);
+    process_item<1, kWaves>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
+                            a.NCp + it.y / a.Cs, lds, bad_page);
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
+}
+
+__device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_rec)[2][kWaves], int (&s_idx)[2], int& bad_page) {
+  const int tid = threadIdx.x;
+  const int n_long = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
+  const int n_work = a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] * a.Hkv;
+  if (n_long >= n_work) return;
+  const int i = tid & 15;
+  const int wave = tid >> 6;
+  if (tid < kWaves) {
+    int i0 = 0, i1 = 0;
+    if (tid == 0) {
+      i0 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], kWaves);
+      i1 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], kWaves);
+      s_idx[0] = i0;
+      s_idx[1] = i1;
+    }
+    i0 = __shfl(i0, 0) + tid;
+    if (i0 < n_work) s_rec[0][tid] = a.suffix_items[i0 / a.Hkv];
+  }
+  __syncthreads();
+  for (int b = 0;; b ^= 1) {
+    const int base = s_idx[b];
+    if (base >= n_work) break;
+    const int qi = base + wave;
+    const int4 it = s_rec[b][wave];
+    __syncthreads();   // everybody has read this round's slots before they are refilled
+    int inew = 0;
+    int4 nrec = make_int4(0, 0, 0, 0);
+    if (tid < kWaves) {
+      const int inext = s_idx[b ^ 1] + tid;
+      if (inext < n_work) nrec = a.suffix_items[inext / a.Hkv];
+      if (tid == 0) inew = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], kWaves);
+    }
+    if (qi < n_work) {   // wave-uniform
+      const int kvh = qi % a.Hkv;
+      const int s = it.x;
+      const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
+      ItemLds<1>* no_lds = nullptr;   // the one-wave path never touches it
+      process_item<1, 1>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
+                         a.NCp + it.y / a.Cs, *no_lds, bad_page);
+    }
+    if (tid < kWaves) {
+      s_rec[b ^ 1][tid] = nrec;
+      if (tid == 0) s_idx[b] = inew;
+    }
+    __syncthreads();
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -556,8 +630,15 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefix_kernel(AttnArgs a) {
   __shared__ PrefixLds lds;
   __shared__ int next_item;
+  __shared__ int s_idx[2];             // short suffix items: first queue index of this / the next round
+  __shared__ int4 s_rec[2][kWaves];    // and their item records
   const int n_work = a.counters[MARL_CTR_NUM_PREFIX_ITEMS] * a.Hkv;
   int bad_page = 0;
+  // The short suffix items go first: each round is a chain of dependent memory accesses with
+  // little data, which is cheap while every workgroup has other work to overlap it with and
+  // expensive at the tail of a kernel, where only a few workgroups are left.
+  short_suffix_items(a, s_rec, s_idx, bad_page);
+  __syncthreads();
   for (;;) {
     if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_PREFIX_CURSOR], 1);
     __syncthreads();
@@ -594,5 +675,4 @@ hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st) {
   hipLaunchKernelGGL(suffix_kernel, dim3(grid), dim3(kAttnThreads), 0, st, a);
   return hipGetLastError();
 }
-
 }  // namespace marl

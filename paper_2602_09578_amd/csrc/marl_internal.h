@@ -11,6 +11,11 @@ constexpr int kPage = 16;        // tokens per page
 constexpr int kD = 128;          // head dimension
 constexpr int kBlockTok = 32;    // tokens one MFMA step of a wave covers (two pages)
 constexpr int kRowsPerQBlock = 128;   // query rows one prefix work item covers
+// suffix items up to this many tokens are handled by one wave (build-time tuning knob)
+#ifndef MARL_SHORT_TOKENS
+#define MARL_SHORT_TOKENS 128
+#endif
+constexpr int kShortTokens = MARL_SHORT_TOKENS;
 constexpr int kAttnThreads = 256;  // 4 waves per workgroup
 constexpr int kPlanThreads = 1024;
 constexpr int kNumClasses = 2048;  // upper bound on cost classes (chunk / 32)

@@ -69,6 +69,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   __shared__ int hist_s[kNumClasses];
   __shared__ int hist_p[kNumClasses];
   __shared__ int tmp[17];
+  __shared__ int n_long_items;
   const int tid = threadIdx.x;
   const int Cs = a.Cs, Cp = a.Cp, R = a.R;
   const int ncls_s = Cs / 32, ncls_p = Cp / 32;
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   for (int i = tid; i < kNumClasses; i += kPlanThreads) { hist_s[i] = 0; hist_p[i] = 0; }
   for (int g = tid; g < a.NG; g += kPlanThreads) a.group_count[g] = 0;
   if (tid < 64) a.counters[tid] = 0;
+  if (tid == 0) n_long_items = 0;
   __threadfence();
   __syncthreads();
 
@@ -92,6 +94,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
     const int nfull = S / Cs, tail = S % Cs;
     if (nfull) atomicAdd(&hist_s[0], nfull);
     if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
+    const int nlong = (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
+    if (nlong) atomicAdd(&n_long_items, nlong);
   }
   __threadfence();
   __syncthreads();
@@ -180,13 +184,165 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   if (tid == 0) {
     a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] = n_suffix_items;
     a.counters[MARL_CTR_NUM_PREFIX_ITEMS] = n_prefix_items;
+    a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] = n_long_items;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Same plan for shapes whose bookkeeping fits in LDS (NS <= 8192, NG <= 2048, chunks <= 8192
+// tokens): inputs are read once into registers, counts, offsets, member lists and histograms
+// live in LDS, and global memory only sees the final stores.  The general kernel above pays
+// a chain of ~30 dependent global round trips; this one pays one.
+// ---------------------------------------------------------------------------------------
+constexpr int kSmallMaxSeqs = 8192;
+constexpr int kSmallMaxGroups = 2048;
+constexpr int kSmallMaxClasses = 256;
+constexpr int kSeqsPerThread = kSmallMaxSeqs / kPlanThreads;
+constexpr int kGroupsPerThread = kSmallMaxGroups / kPlanThreads;
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
+  __shared__ int cnt[kSmallMaxGroups];
+  __shared__ int start[kSmallMaxGroups + 1];
+  __shared__ int members[kSmallMaxSeqs];
+  __shared__ int hist_s[kSmallMaxClasses];
+  __shared__ int hist_p[kSmallMaxClasses];
+  __shared__ int tmp[17];
+  __shared__ int n_long_items;
+  const int tid = threadIdx.x;
+  const int Cs = a.Cs, Cp = a.Cp, R = a.R;
+  const int ncls_s = Cs / 32, ncls_p = Cp / 32;
+  const int max_st = a.max_sp * kPage, max_pt = a.max_pp * kPage;
+  int flags = 0;
+
+  // inputs -> registers (the only loads from global memory)
+  int g_of[kSeqsPerThread], S_of[kSeqsPerThread], rank_of[kSeqsPerThread];
+#pragma unroll
+  for (int k = 0; k < kSeqsPerThread; ++k) {
+    const int s = tid + k * kPlanThreads;
+    g_of[k] = s < a.NS ? a.group_of_seq[s] : -1;
+    S_of[k] = s < a.NS ? a.suffix_lens[s] : 0;
+  }
+  int P_of[kGroupsPerThread];
+#pragma unroll
+  for (int k = 0; k < kGroupsPerThread; ++k) {
+    const int g = tid + k * kPlanThreads;
+    P_of[k] = g < a.NG ? a.prefix_lens[g] : 0;
+  }
+  for (int i = tid; i < kSmallMaxGroups; i += kPlanThreads) cnt[i] = 0;
+  for (int i = tid; i < kSmallMaxClasses; i += kPlanThreads) { hist_s[i] = 0; hist_p[i] = 0; }
+  if (tid == 0) n_long_items = 0;
+  if (tid < 64) a.counters[tid] = 0;
+  __syncthreads();
+
+#pragma unroll
+  for (int k = 0; k < kSeqsPerThread; ++k) {
+    const int s = tid + k * kPlanThreads;
+    rank_of[k] = -1;
+    if (s < a.NS) {
+      if ((unsigned)g_of[k] < (unsigned)a.NG) rank_of[k] = atomicAdd(&cnt[g_of[k]], 1);
+      else flags |= MARL_FLAG_BAD_GROUP;
+      S_of[k] = clamp_len(S_of[k], max_st, flags);
+      const int nfull = S_of[k] / Cs, tail = S_of[k] % Cs;
+      if (nfull) atomicAdd(&hist_s[0], nfull);
+      if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
+      const int nlong = (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
+      if (nlong) atomicAdd(&n_long_items, nlong);
+    }
+  }
+  __syncthreads();
+  const int nseq_grouped = block_exclusive_scan<false>(cnt, start, a.NG, tmp);
+  if (tid == 0) start[a.NG] = nseq_grouped;
+
+#pragma unroll
+  for (int k = 0; k < kGroupsPerThread; ++k) {
+    const int g = tid + k * kPlanThreads;
+    if (g < a.NG) {
+      P_of[k] = clamp_len(P_of[k], max_pt, flags);
+      const int nqb = (cnt[g] * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+      const int nfull = P_of[k] / Cp, tail = P_of[k] % Cp;
+      if (nqb) {
+        if (nfull) atomicAdd(&hist_p[0], nfull * nqb);
+        if (tail) atomicAdd(&hist_p[(Cp - tail) / 32], nqb);
+      }
+    }
+  }
+  __syncthreads();
+  const int n_suffix_items = block_exclusive_scan<false>(hist_s, hist_s, ncls_s, tmp);
+  const int n_prefix_items = block_exclusive_scan<false>(hist_p, hist_p, ncls_p, tmp);
+
+#pragma unroll
+  for (int k = 0; k < kSeqsPerThread; ++k) {
+    const int s = tid + k * kPlanThreads;
+    if (s < a.NS) {
+      if (rank_of[k] >= 0) members[start[g_of[k]] + rank_of[k]] = s;
+      const int S = S_of[k];
+      const int nfull = S / Cs, tail = S % Cs;
+      if (nfull) {
+        const int pos = atomicAdd(&hist_s[0], nfull);
+        for (int i = 0; i < nfull; ++i) a.suffix_items[pos + i] = make_int4(s, i * Cs, (i + 1) * Cs, 0);
+      }
+      if (tail) {
+        const int pos = atomicAdd(&hist_s[(Cs - tail) / 32], 1);
+        a.suffix_items[pos] = make_int4(s, nfull * Cs, S, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < kGroupsPerThread; ++k) {
+    const int g = tid + k * kPlanThreads;
+    if (g < a.NG) {
+      a.group_count[g] = cnt[g];
+      a.group_start[g] = start[g];
+      const int P = P_of[k];
+      const int nqb = (cnt[g] * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+      const int nfull = P / Cp, tail = P % Cp;
+      if (nqb) {
+        if (nfull) {
+          const int pos = atomicAdd(&hist_p[0], nfull * nqb);
+          for (int i = 0; i < nfull; ++i)
+            for (int b = 0; b < nqb; ++b)
+              a.prefix_items[pos + i * nqb + b] = make_int4(g, i * Cp, (i + 1) * Cp, b * kRowsPerQBlock);
+        }
+        if (tail) {
+          const int pos = atomicAdd(&hist_p[(Cp - tail) / 32], nqb);
+          for (int b = 0; b < nqb; ++b)
+            a.prefix_items[pos + b] = make_int4(g, nfull * Cp, P, b * kRowsPerQBlock);
+        }
+      }
+    }
+  }
+  if (tid == 0) a.group_start[a.NG] = nseq_grouped;
+  __syncthreads();
+
+  // ascending sequence id inside every group of at most 64 members (as in the general kernel)
+#pragma unroll
+  for (int k = 0; k < kSeqsPerThread; ++k) {
+    const int s = tid + k * kPlanThreads;
+    if (s < a.NS && rank_of[k] >= 0) {
+      const int b = start[g_of[k]], n = cnt[g_of[k]];
+      int place = rank_of[k];
+      if (n <= 64) {
+        place = 0;
+        for (int m = 0; m < n; ++m) place += members[b + m] < s;
+      }
+      a.group_seqs[b + place] = s;
+    }
+  }
+  if (flags) atomicOr(&a.counters[MARL_CTR_FLAGS], flags);
+  if (tid == 0) {
+    a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] = n_suffix_items;
+    a.counters[MARL_CTR_NUM_PREFIX_ITEMS] = n_prefix_items;
+    a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] = n_long_items;
   }
 }
 
 }  // namespace
 
 hipError_t launch_plan(const AttnArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
+  const bool small = a.NS <= kSmallMaxSeqs && a.NG <= kSmallMaxGroups &&
+                     a.Cs / 32 <= kSmallMaxClasses && a.Cp / 32 <= kSmallMaxClasses;
+  if (small) hipLaunchKernelGGL(plan_kernel_small, dim3(1), dim3(kPlanThreads), 0, st, a);
+  else hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
   return hipGetLastError();
 }
 

@@ -86,6 +86,17 @@ def test_big_group_many_query_blocks():
     check_attn(inp, B.MARL_OUT_F32)
 
 
+def test_many_groups_use_the_general_plan_kernel():
+    """More groups than the LDS-resident plan kernel handles (2048)."""
+    print("case: many groups", flush=True)
+    rng = np.random.default_rng(21)
+    NG = 2100
+    sizes = rng.integers(1, 3, NG)
+    gos = np.repeat(np.arange(NG), sizes)
+    inp = custom_inputs(rng.integers(0, 40, NG), rng.integers(0, 50, len(gos)), gos, 4, 2, seed=23)
+    check_attn(inp, B.MARL_OUT_F32)
+
+
 def test_negative_and_zero_scale():
     print("case: scale sign", flush=True)
     for scale in (-0.11, 0.0):

@@ -40,6 +40,11 @@ def compare(shape, pl, sl, gos, Hq, Hkv):
     assert np.array_equal(got["seqs"][:n], want.group_seqs[:n])
     assert got["ctr"][B.CTR_FLAGS] == want.flags
     assert got["ctr"][B.CTR_SUFFIX_CURSOR] == 0 and got["ctr"][B.CTR_PREFIX_CURSOR] == 0
+    assert got["ctr"][B.CTR_SHORT_CURSOR] == 0
+    nlong = got["ctr"][B.CTR_NUM_LONG_SUFFIX_ITEMS]
+    assert nlong == want.num_long_suffix_items
+    assert all(it[2] - it[1] > plan_ref.SHORT_TOKENS for it in got["sitems"][:nlong].tolist())
+    assert all(it[2] - it[1] <= plan_ref.SHORT_TOKENS for it in got["sitems"][nlong:].tolist())
     for items, ref_items, chunk in ((got["sitems"], want.suffix_items, want.Cs),
                                     (got["pitems"], want.prefix_items, want.Cp)):
         assert sorted(map(tuple, items.tolist())) == sorted(ref_items)
@@ -83,3 +88,18 @@ def test_plan_large_group_stays_a_valid_set():
     assert list(got["count"]) == [100, 100] and list(got["start"]) == [0, 100, 200]
     assert sorted(got["seqs"][:100]) == sorted(np.nonzero(gos == 0)[0])
     assert sorted(got["seqs"][100:]) == sorted(np.nonzero(gos == 1)[0])
+
+
+def test_plan_general_kernel_for_shapes_beyond_the_lds_variant():
+    """More than 8192 sequences / 2048 groups: the plan kernel that keeps its bookkeeping in
+    global memory runs; same contract."""
+    print("case: plan big", flush=True)
+    rng = np.random.default_rng(11)
+    NG = 2500
+    sizes = rng.integers(1, 8, NG)
+    gos = rng.permutation(np.repeat(np.arange(NG), sizes)).astype(np.int32)
+    assert len(gos) > 8192
+    pl = rng.integers(0, 400, NG).astype(np.int32)
+    sl = rng.integers(0, 700, len(gos)).astype(np.int32)
+    shape = B.make_shape(len(gos), NG, 8, 2, 10, 25, 44, suffix_chunk_tokens=256, prefix_chunk_tokens=128)
+    compare(shape, pl, sl, gos, 8, 2)
