@@ -98,9 +98,11 @@ enum {
 };
 
 /* Fills *layout for *shape.  Host-only, no GPU needed.
- * Chunking rule when the shape gives 0:  Cs starts at 2048 and is halved while
- * NS*Hkv*ceil(max_suffix_tokens/Cs) < 2048 and Cs > 256;  Cp starts at 1024 and is halved
- * while NG*Hkv*ceil(max_prefix_tokens/Cp) < 1024 and Cp > 256. */
+ * Chunking rule when the shape gives 0:  Cs starts at 8192 and is halved while
+ * NS*Hkv*ceil(max_suffix_tokens/Cs) < 2048 and Cs > 256;  Cp starts at 8192 and is halved
+ * while NG*Hkv*Q*ceil(max_prefix_tokens/Cp) < 512 and Cp > 256, where
+ * Q = max(1, ceil(ceil(NS/NG)*(Hq/Hkv) / rows_per_qblock)) estimates the query-row blocks of
+ * a group. */
 int marl_attn_plan_layout_for(const marl_attn_shape* shape, marl_attn_plan_layout* layout);
 
 /* *bytes = layout.total_bytes (an upper bound that depends on the shape only). Host-only. */

@@ -23,18 +23,20 @@ def _ceil_div(a: int, b: int) -> int:
     return -(-a // b)
 
 
-def default_chunks(NS: int, NG: int, Hkv: int, max_prefix_pages: int, max_suffix_pages: int,
+def default_chunks(NS: int, NG: int, Hq: int, Hkv: int, max_prefix_pages: int, max_suffix_pages: int,
                    suffix_chunk: int = 0, prefix_chunk: int = 0) -> Tuple[int, int]:
     mst, mpt = max_suffix_pages * PAGE, max_prefix_pages * PAGE
     Cs = suffix_chunk
     if Cs == 0:
-        Cs = 2048
+        Cs = 8192
         while NS * Hkv * _ceil_div(mst, Cs) < 2048 and Cs > 256:
             Cs //= 2
     Cp = prefix_chunk
     if Cp == 0:
-        Cp = 1024
-        while NG * Hkv * _ceil_div(mpt, Cp) < 1024 and Cp > 256:
+        rows = _ceil_div(NS, NG) * (Hq // Hkv) if NG > 0 else 0
+        qblocks = max(1, _ceil_div(rows, ROWS_PER_QBLOCK))
+        Cp = 8192
+        while NG * Hkv * qblocks * _ceil_div(mpt, Cp) < 512 and Cp > 256:
             Cp //= 2
     return Cs, Cp
 
@@ -64,7 +66,7 @@ def build_plan(prefix_lens, suffix_lens, group_of_seq, Hq: int, Hkv: int, max_pr
     gos = np.asarray(group_of_seq, dtype=np.int64)
     NS, NG = len(sl), len(pl)
     R = Hq // Hkv
-    Cs, Cp = default_chunks(NS, NG, Hkv, max_prefix_pages, max_suffix_pages, suffix_chunk, prefix_chunk)
+    Cs, Cp = default_chunks(NS, NG, Hq, Hkv, max_prefix_pages, max_suffix_pages, suffix_chunk, prefix_chunk)
     mst, mpt = max_suffix_pages * PAGE, max_prefix_pages * PAGE
     flags = 0
     members: List[List[int]] = [[] for _ in range(NG)]

@@ -48,15 +48,19 @@ int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
   memset(L, 0, sizeof *L);
   const long NS = s->num_seqs, NG = s->num_groups, Hkv = s->num_kv_heads, Hq = s->num_q_heads;
   const long mst = (long)s->max_suffix_pages * marl::kPage, mpt = (long)s->max_prefix_pages * marl::kPage;
+  // Default chunks: as large as possible (every work item costs a fixed few microseconds and
+  // one partial per query row) while the shape still promises enough items to fill the GPU.
   long Cs = s->suffix_chunk_tokens;
   if (Cs == 0) {
-    Cs = 2048;
+    Cs = 8192;
     while (NS * Hkv * ceil_div(mst, Cs) < 2048 && Cs > 256) Cs /= 2;
   }
   long Cp = s->prefix_chunk_tokens;
   if (Cp == 0) {
-    Cp = 1024;
-    while (NG * Hkv * ceil_div(mpt, Cp) < 1024 && Cp > 256) Cp /= 2;
+    const long rows = NG > 0 ? ceil_div(NS, NG) * (Hq / Hkv) : 0;   // query rows of an average group
+    const long qblocks = rows > marl::kRowsPerQBlock ? ceil_div(rows, marl::kRowsPerQBlock) : 1;
+    Cp = 8192;
+    while (NG * Hkv * qblocks * ceil_div(mpt, Cp) < 512 && Cp > 256) Cp /= 2;
   }
   const long NCs = ceil_div(mst, Cs) > 1 ? ceil_div(mst, Cs) : 1;
   const long NCp = ceil_div(mpt, Cp) > 1 ? ceil_div(mpt, Cp) : 1;
@@ -115,6 +119,7 @@ struct StageTimer {
 };
 
 int g_num_cus = 0, g_prefix_bpc = 0, g_suffix_bpc = 0;
+
 std::once_flag g_dev_once;
 hipError_t g_dev_err = hipSuccess;
 

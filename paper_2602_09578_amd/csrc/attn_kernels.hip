@@ -64,6 +64,20 @@ __device__ __forceinline__ u32x4 ld_stream(const char* p) {
   return *reinterpret_cast<const u32x4*>(p);
 #endif
 }
+// K rows are fetched as 16 x 64 B per instruction, so every 128-byte line is touched by two
+// consecutive instructions: K uses ordinary (cached) loads so that the second touch hits the
+// vector cache; measured on a load-only replica of this pattern: 6.3 TB/s with non-temporal K,
+// 6.9 TB/s with cached K and non-temporal V.
+#ifndef MARL_NT_K
+#define MARL_NT_K 0
+#endif
+__device__ __forceinline__ u32x4 ld_stream_k(const char* p) {
+#if MARL_NT_K
+  return ld_stream(p);
+#else
+  return *reinterpret_cast<const u32x4*>(p);
+#endif
+}
 
 // LDS per workgroup: (max, sum) of every wave and one buffer for a wave's accumulators.
 template <int MT>
@@ -138,7 +152,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
     for (int T = 0; T < 2; ++T)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kr[T][kk] = ld_stream(kp + T * (4 * kD * 2) + kk * 64);
+        kr[T][kk] = ld_stream_k(kp + T * (4 * kD * 2) + kk * 64);
   };
   auto issue_v = [&](int p0, int p1) {
     const char* vp = vbase + (size_t)(j < 2 ? p0 : p1) * page_bytes;
@@ -265,10 +279,10 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
     for (int qt = 0; qt < MT; ++qt) {
       float mm = lds.m[0][qt * 16 + i];
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, lds.m[w][qt * 16 + i]);
+      for (int w = 1; w < NW; ++w) mm = fmaxf(mm, lds.m[w][qt * 16 + i]);
       float ll = 0.f;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
+      for (int w = 0; w < NW; ++w) {
         const float mw = lds.m[w][qt * 16 + i];
         const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
         ll += lds.l[w][qt * 16 + i] * f;
@@ -279,7 +293,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
 #pragma unroll
       for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= f_own;
     }
-    for (int w = 1; w < kWaves; ++w) {
+    for (int w = 1; w < NW; ++w) {
       if (wave == w) {
 #pragma unroll
         for (int qt = 0; qt < MT; ++qt)
@@ -330,7 +344,16 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
 //                        own it cost one more launch per call, and at the end of any kernel
 //                        its latency-bound rounds stretch the tail.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kAttnThreads) void suffix_kernel(AttnArgs a) {
+#ifndef MARL_SUFFIX_WAVES_PER_EU
+#define MARL_SUFFIX_WAVES_PER_EU 3
+#endif
+#ifndef MARL_SUFFIX_WAVES
+#define MARL_SUFFIX_WAVES 4
+#endif
+constexpr int kSuffixWaves = MARL_SUFFIX_WAVES;   // waves that share one long item (= workgroup size / 64)
+__global__ __launch_bounds__(kSuffixWaves * 64)
+__attribute__((amdgpu_waves_per_eu(MARL_SUFFIX_WAVES_PER_EU, MARL_SUFFIX_WAVES_PER_EU)))
+void suffix_kernel(AttnArgs a) {
   __shared__ ItemLds<1> lds;
   __shared__ int next_item;
   const int n_work = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
@@ -346,8 +369,8 @@ __global__ __launch_bounds__(kAttnThreads) void suffix_kernel(AttnArgs a) {
     const int s = it.x;
     const int i = threadIdx.x & 15;
     const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
-    process_item<1, kWaves>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
-                            a.NCp + it.y / a.Cs, lds, bad_page);
+    process_item<1, kSuffixWaves>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
+                                  a.NCp + it.y / a.Cs, lds, bad_page);
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }
@@ -408,8 +431,8 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_r
 // wave sees all tokens, so the group's K/V must reach all four: each 32-token step (two
 // pages, 16 KB of K and V) is fetched once by the workgroup with fully coalesced 16-byte
 // loads (a wave reads 1 KB contiguous per instruction), staged in registers, written to a
-// double-buffered LDS tile and read back in MFMA operand layout.  Loads run two steps
-// ahead (32 KB in flight per workgroup).  No cross-wave reduction is needed.
+// triple-buffered LDS tile and read back in MFMA operand layout.  Loads run three steps
+// ahead (48 KB in flight per workgroup).  No cross-wave reduction is needed.
 //
 // LDS tile of one step (16 KB): K as 32 token rows of 256 B, the 16-byte chunk index of
 // row tau XOR-ed with (tau&3)|((tau>>1)&4) so that the 8 lanes of an operand read hit 8
@@ -418,7 +441,7 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_r
 // ---------------------------------------------------------------------------------------
 constexpr int kStepBytes = 2 * kBlockTok * kD * 2;   // K + V of one 32-token step
 struct PrefixLds {
-  __attribute__((aligned(16))) char buf[2][kStepBytes];
+  __attribute__((aligned(16))) char buf[3][kStepBytes];
 };
 
 template <int MTW>
@@ -585,27 +608,38 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
       }
   };
 
-  u32x4 stA[4], stB[4];
+  // Three register stages and three LDS buffers: while step n is computed from buffer n%3,
+  // the loads of steps n+1, n+2 and n+3 are in flight (48 KB per workgroup); step n+1 moves
+  // from its registers to buffer (n+1)%3 at the end of the iteration, one barrier per step.
+  u32x4 st0[4], st1[4], st2[4];
   int p0, p1;
   load_ids(0, p0, p1);
-  issue(p0, p1, stA);
+  issue(p0, p1, st0);
   load_ids(1, p0, p1);
-  issue(p0, p1, stB);
+  issue(p0, p1, st1);
   load_ids(2, p0, p1);
-  stage_to_lds(stA, lds.buf[0]);
+  issue(p0, p1, st2);
+  load_ids(3, p0, p1);
+  stage_to_lds(st0, lds.buf[0]);
   __syncthreads();
-  for (int n = 0; n < nsteps; n += 2) {
-    // even step: refill A (two steps ahead), compute from buffer 0, hand B to buffer 1
-    issue(p0, p1, stA);
-    load_ids(n + 3, p0, p1);
+  for (int n = 0; n < nsteps; n += 3) {
+    issue(p0, p1, st0);          // step n+3
+    load_ids(n + 4, p0, p1);
     compute(n, lds.buf[0]);
-    stage_to_lds(stB, lds.buf[1]);
+    stage_to_lds(st1, lds.buf[1]);
     __syncthreads();
     if (n + 1 < nsteps) {
-      issue(p0, p1, stB);
-      load_ids(n + 4, p0, p1);
+      issue(p0, p1, st1);        // step n+4
+      load_ids(n + 5, p0, p1);
       compute(n + 1, lds.buf[1]);
-      stage_to_lds(stA, lds.buf[0]);
+      stage_to_lds(st2, lds.buf[2]);
+      __syncthreads();
+    }
+    if (n + 2 < nsteps) {
+      issue(p0, p1, st2);        // step n+5
+      load_ids(n + 6, p0, p1);
+      compute(n + 2, lds.buf[2]);
+      stage_to_lds(st0, lds.buf[0]);
       __syncthreads();
     }
   }
@@ -627,7 +661,12 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   }
 }
 
-__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefix_kernel(AttnArgs a) {
+#ifndef MARL_PREFIX_WAVES_PER_EU
+#define MARL_PREFIX_WAVES_PER_EU 2
+#endif
+__global__ __launch_bounds__(kAttnThreads)
+__attribute__((amdgpu_waves_per_eu(MARL_PREFIX_WAVES_PER_EU, MARL_PREFIX_WAVES_PER_EU)))
+void prefix_kernel(AttnArgs a) {
   __shared__ PrefixLds lds;
   __shared__ int next_item;
   __shared__ int s_idx[2];             // short suffix items: first queue index of this / the next round
@@ -648,7 +687,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2,
     const int4 it = a.prefix_items[qi / a.Hkv];
     const int kvh = qi % a.Hkv;
     const int rows = min(kRowsPerQBlock, a.group_count[it.x] * a.R - it.w);
-    if (rows <= 16 * kWaves) prefix_item<1>(a, it, kvh, lds, bad_page);   // workgroup-uniform
+    if (kRowsPerQBlock <= 16 * kWaves || rows <= 16 * kWaves) prefix_item<1>(a, it, kvh, lds, bad_page);   // workgroup-uniform
     else prefix_item<2>(a, it, kvh, lds, bad_page);
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
@@ -663,7 +702,7 @@ int prefix_blocks_per_cu() {
 }
 int suffix_blocks_per_cu() {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, suffix_kernel, kAttnThreads, 0) != hipSuccess || n < 1) n = 1;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, suffix_kernel, kSuffixWaves * 64, 0) != hipSuccess || n < 1) n = 1;
   return n;
 }
 
@@ -672,7 +711,7 @@ hipError_t launch_prefix(const AttnArgs& a, int grid, hipStream_t st) {
   return hipGetLastError();
 }
 hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st) {
-  hipLaunchKernelGGL(suffix_kernel, dim3(grid), dim3(kAttnThreads), 0, st, a);
+  hipLaunchKernelGGL(suffix_kernel, dim3(grid), dim3(kSuffixWaves * 64), 0, st, a);
   return hipGetLastError();
 }
 }  // namespace marl

@@ -10,7 +10,11 @@ namespace marl {
 constexpr int kPage = 16;        // tokens per page
 constexpr int kD = 128;          // head dimension
 constexpr int kBlockTok = 32;    // tokens one MFMA step of a wave covers (two pages)
-constexpr int kRowsPerQBlock = 128;   // query rows one prefix work item covers
+// query rows one prefix work item covers: 64 (one 16-row tile per wave) or 128 (two)
+#ifndef MARL_ROWS_PER_QBLOCK
+#define MARL_ROWS_PER_QBLOCK 128
+#endif
+constexpr int kRowsPerQBlock = MARL_ROWS_PER_QBLOCK;
 // suffix items up to this many tokens are handled by one wave (build-time tuning knob)
 #ifndef MARL_SHORT_TOKENS
 #define MARL_SHORT_TOKENS 128

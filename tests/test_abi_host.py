@@ -52,7 +52,7 @@ def test_layout_and_default_chunks():
     assert L.partial_o_off + 16 * 8 * 2 * 128 * 4 <= L.total_bytes
     big = B.marl_attn_plan_layout_for(good_shape(num_seqs=2048, num_groups=256, num_q_heads=28, num_kv_heads=4,
                                                  max_prefix_pages=128, max_suffix_pages=512))
-    assert (big.suffix_chunk_tokens, big.prefix_chunk_tokens, big.suffix_slots, big.prefix_slots) == (2048, 1024, 4, 2)
+    assert (big.suffix_chunk_tokens, big.prefix_chunk_tokens, big.suffix_slots, big.prefix_slots) == (8192, 8192, 1, 1)
     ov = B.marl_attn_plan_layout_for(good_shape(suffix_chunk_tokens=64, prefix_chunk_tokens=96))
     assert (ov.suffix_chunk_tokens, ov.prefix_chunk_tokens, ov.suffix_slots, ov.prefix_slots) == (64, 96, 2, 3)
 

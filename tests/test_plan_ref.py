@@ -42,7 +42,9 @@ def test_clamping_and_bad_group_flags():
 
 
 def test_default_chunk_rule():
-    assert plan_ref.default_chunks(2048, 256, 4, 128, 512) == (2048, 1024)
-    assert plan_ref.default_chunks(16, 4, 2, 16, 8) == (256, 256)
-    assert plan_ref.default_chunks(256, 64, 8, 512, 1536) == (2048, 1024)
-    assert plan_ref.default_chunks(16, 4, 2, 16, 8, 64, 96) == (64, 96)
+    assert plan_ref.default_chunks(2048, 256, 28, 4, 128, 512) == (8192, 8192)
+    assert plan_ref.default_chunks(16, 4, 8, 2, 16, 8) == (256, 256)
+    assert plan_ref.default_chunks(256, 64, 64, 8, 512, 1536) == (8192, 8192)
+    assert plan_ref.default_chunks(2048, 64, 28, 4, 256, 4) == (8192, 8192)      # 224 rows: two row blocks
+    assert plan_ref.default_chunks(64, 8, 8, 2, 256, 512) == (512, 256)
+    assert plan_ref.default_chunks(16, 4, 8, 2, 16, 8, 64, 96) == (64, 96)
