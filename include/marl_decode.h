@@ -75,6 +75,7 @@ typedef struct marl_attn_plan_layout {
   size_t seq_rank_off;           /* int32[NS]   scratch */
   size_t group_tmp_off;          /* int32[NS]   scratch */
   size_t group_seqs_off;         /* int32[NS]   sequence ids grouped by group (CSR values) */
+  size_t seq_chunks_off;         /* int32[NS]   prefix chunks | suffix chunks << 16 of each sequence */
   size_t suffix_items_off;       /* int32[max_suffix_items][4] {seq, tok_begin, tok_end, 0} */
   size_t prefix_items_off;       /* int32[max_prefix_items][4] {group, tok_begin, tok_end, row_begin} */
   size_t partial_ml_off;         /* float[NS][Hq][NCp+NCs][2]  (max, sum) per partial */

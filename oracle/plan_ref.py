@@ -53,6 +53,7 @@ class PlanRef:
     suffix_items: List[Tuple[int, int, int, int]]   # (seq, tok_begin, tok_end, 0)
     prefix_items: List[Tuple[int, int, int, int]]   # (group, tok_begin, tok_end, row_begin)
     flags: int
+    seq_chunks: np.ndarray = None   # int32 [NS]: prefix chunks | suffix chunks << 16
 
     @property
     def num_long_suffix_items(self) -> int:
@@ -102,8 +103,14 @@ def build_plan(prefix_lens, suffix_lens, group_of_seq, Hq: int, Hkv: int, max_pr
         for t0 in range(0, P, Cp):
             for r0 in range(0, rows, ROWS_PER_QBLOCK):
                 pitems.append((g, t0, min(P, t0 + Cp), r0))
+    chunks = np.zeros(NS, dtype=np.int32)
+    for s in range(NS):
+        g = int(gos[s])
+        P = min(max(int(pl[g]), 0), mpt) if 0 <= g < NG else 0
+        S = min(max(int(sl[s]), 0), mst)
+        chunks[s] = _ceil_div(P, Cp) | (_ceil_div(S, Cs) << 16)
     return PlanRef(Cs, Cp, max(1, _ceil_div(mst, Cs)), max(1, _ceil_div(mpt, Cp)),
-                   count, start, seqs, sitems, pitems, flags)
+                   count, start, seqs, sitems, pitems, flags, chunks)
 
 
 def cost_class(item, chunk: int) -> int:

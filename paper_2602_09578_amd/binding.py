@@ -36,6 +36,7 @@ class PlanLayout(ctypes.Structure):
         "rows_per_qblock", "max_suffix_items", "max_prefix_items", "reserved")] + \
         [(n, SZ) for n in (
             "counters_off", "group_count_off", "group_start_off", "seq_rank_off", "group_tmp_off", "group_seqs_off",
+            "seq_chunks_off",
             "suffix_items_off", "prefix_items_off", "partial_ml_off", "partial_o_off", "total_bytes")]
 
 

@@ -68,6 +68,7 @@ int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
   const long max_s_items = NS * NCs;
   const long max_p_items = (NG + NS * R / marl::kRowsPerQBlock + 1) * NCp;
   if (max_s_items >= (1L << 28) || max_p_items >= (1L << 28)) return MARL_UNSUPPORTED;
+  if (NCs >= (1L << 15) || NCp >= (1L << 15)) return MARL_UNSUPPORTED;   // packed into 16 bits each
   L->suffix_chunk_tokens = (int32_t)Cs;
   L->prefix_chunk_tokens = (int32_t)Cp;
   L->suffix_slots = (int32_t)NCs;
@@ -83,6 +84,7 @@ int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
   L->seq_rank_off = take((size_t)NS * 4);
   L->group_tmp_off = take((size_t)NS * 4);
   L->group_seqs_off = take((size_t)NS * 4);
+  L->seq_chunks_off = take((size_t)NS * 4);
   L->suffix_items_off = take((size_t)max_s_items * 16);
   L->prefix_items_off = take((size_t)max_p_items * 16);
   L->partial_ml_off = take((size_t)NS * Hq * (NCp + NCs) * 8);
@@ -150,6 +152,7 @@ int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArg
   a.seq_rank = reinterpret_cast<int32_t*>(w + L.seq_rank_off);
   a.group_tmp = reinterpret_cast<int32_t*>(w + L.group_tmp_off);
   a.group_seqs = reinterpret_cast<int32_t*>(w + L.group_seqs_off);
+  a.seq_chunks = reinterpret_cast<int32_t*>(w + L.seq_chunks_off);
   a.suffix_items = reinterpret_cast<int4*>(w + L.suffix_items_off);
   a.prefix_items = reinterpret_cast<int4*>(w + L.prefix_items_off);
   a.partial_ml = reinterpret_cast<float2*>(w + L.partial_ml_off);

@@ -40,6 +40,7 @@ struct AttnArgs {
   int32_t* seq_rank;
   int32_t* group_tmp;
   int32_t* group_seqs;
+  int32_t* seq_chunks;   // per sequence: prefix chunk count | suffix chunk count << 16
   int4* suffix_items;
   int4* prefix_items;
   float2* partial_ml;

@@ -127,6 +127,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
     if (rank >= 0) a.group_tmp[ld_agent(a.group_start + a.group_of_seq[s]) + rank] = s;
     int dummy = 0;
     const int S = clamp_len(a.suffix_lens[s], max_st, dummy);
+    const int P = rank >= 0 ? clamp_len(a.prefix_lens[a.group_of_seq[s]], max_pt, dummy) : 0;
+    a.seq_chunks[s] = ((P + Cp - 1) / Cp) | (((S + Cs - 1) / Cs) << 16);
     const int nfull = S / Cs, tail = S % Cs;
     if (nfull) {
       const int pos = atomicAdd(&hist_s[0], nfull);
@@ -276,6 +278,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
     if (s < a.NS) {
       if (rank_of[k] >= 0) members[start[g_of[k]] + rank_of[k]] = s;
       const int S = S_of[k];
+      int dummy = 0;
+      const int P = rank_of[k] >= 0 ? clamp_len(a.prefix_lens[g_of[k]], max_pt, dummy) : 0;
+      a.seq_chunks[s] = ((P + Cp - 1) / Cp) | (((S + Cs - 1) / Cs) << 16);
       const int nfull = S / Cs, tail = S % Cs;
       if (nfull) {
         const int pos = atomicAdd(&hist_s[0], nfull);

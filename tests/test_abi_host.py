@@ -46,7 +46,7 @@ def test_layout_and_default_chunks():
     assert (L.suffix_chunk_tokens, L.prefix_chunk_tokens) == (256, 256)
     assert (L.suffix_slots, L.prefix_slots, L.rows_per_qblock) == (1, 1, 128)
     assert L.total_bytes == B.marl_workspace_bytes(good_shape())
-    offs = [L.counters_off, L.group_count_off, L.group_start_off, L.seq_rank_off, L.group_tmp_off, L.group_seqs_off,
+    offs = [L.counters_off, L.group_count_off, L.group_start_off, L.seq_rank_off, L.group_tmp_off, L.group_seqs_off, L.seq_chunks_off,
             L.suffix_items_off, L.prefix_items_off, L.partial_ml_off, L.partial_o_off, L.total_bytes]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and offs[0] == 0
     assert L.partial_o_off + 16 * 8 * 2 * 128 * 4 <= L.total_bytes

@@ -22,7 +22,7 @@ def read_plan(shape, prefix_lens, suffix_lens, gos):
     ctr = i32(L.counters_off, 64)
     NS, NG = shape.num_seqs, shape.num_groups
     return dict(L=L, ctr=ctr, count=i32(L.group_count_off, NG), start=i32(L.group_start_off, NG + 1),
-                seqs=i32(L.group_seqs_off, NS),
+                seqs=i32(L.group_seqs_off, NS), chunks=i32(L.seq_chunks_off, NS),
                 sitems=i32(L.suffix_items_off, 4 * ctr[0]).reshape(-1, 4),
                 pitems=i32(L.prefix_items_off, 4 * ctr[1]).reshape(-1, 4))
 
@@ -39,6 +39,7 @@ def compare(shape, pl, sl, gos, Hq, Hkv):
     n = int(want.group_start[-1])
     assert np.array_equal(got["seqs"][:n], want.group_seqs[:n])
     assert got["ctr"][B.CTR_FLAGS] == want.flags
+    assert np.array_equal(got["chunks"], want.seq_chunks)
     assert got["ctr"][B.CTR_SUFFIX_CURSOR] == 0 and got["ctr"][B.CTR_PREFIX_CURSOR] == 0
     assert got["ctr"][B.CTR_SHORT_CURSOR] == 0
     nlong = got["ctr"][B.CTR_NUM_LONG_SUFFIX_ITEMS]
