@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen7b", choices=sorted(I.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seq-stride", type=int, default=1, help="CPU baseline: every n-th sequence")
+    ap.add_argument("--cpu-logprob-rows", type=int, default=1 << 30, help="CPU baseline: first n logit rows")
     ap.add_argument("--suffix-chunk", type=int, default=0)
     ap.add_argument("--prefix-chunk", type=int, default=0)
     a = ap.parse_args()
@@ -132,7 +134,7 @@ def main():
                      "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": None},
     }
     if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=4, lp_rows=256)
+        res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
     print(json.dumps(res))
 
 

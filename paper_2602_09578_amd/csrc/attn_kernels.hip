@@ -46,6 +46,24 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 
 constexpr int kWaves = kAttnThreads / 64;
 
+// All-reduce over the four lanes l, l^16, l^32, l^48 (the lanes that share a q-row) with the
+// gfx950 row-swap instructions, which stay in the vector ALU (a shuffle through the LDS
+// crossbar costs a round trip in the middle of the softmax dependency chain).
+// permlane16_swap(x, x) yields (rows 0,0,2,2 ; rows 1,1,3,3) of x; permlane32_swap(x, x)
+// yields (rows 0,1,0,1 ; rows 2,3,2,3).
+__device__ __forceinline__ float rows_allreduce_max(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_allreduce_sum(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // Wave-uniform read of read-only input through the scalar cache.
 __device__ __forceinline__ int ld_uniform(const int32_t* p) {
   return *reinterpret_cast<const int32_t __attribute__((address_space(4)))*>(
@@ -210,8 +228,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
       const f32x4 s0 = s[qt][0], s1 = s[qt][1];
       float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                        fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = rows_allreduce_max(mx);
       const float m_new = fmaxf(m_run[qt], mx * sc);
       const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
       float p[8];
@@ -254,8 +271,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
   // the four lanes that share a q-row each hold a part of its sum
 #pragma unroll
   for (int qt = 0; qt < MT; ++qt) {
-    l_run[qt] += __shfl_xor(l_run[qt], 16);
-    l_run[qt] += __shfl_xor(l_run[qt], 32);
+    l_run[qt] = rows_allreduce_sum(l_run[qt]);
   }
 
   float m_all[MT], l_all[MT];
@@ -563,8 +579,7 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
           }
           float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                            fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-          mx = fmaxf(mx, __shfl_xor(mx, 16));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          mx = rows_allreduce_max(mx);
           const float m_new = fmaxf(m_run[qt], mx * sc);
           const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
           float p[8];
@@ -648,9 +663,7 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
 
 #pragma unroll
   for (int qt = 0; qt < MTW; ++qt) {
-    float l = l_run[qt];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    const float l = rows_allreduce_sum(l_run[qt]);
     if (row_index[qt] >= 0) {
       const size_t ps = (size_t)row_index[qt] * nslot + slot;
       float* dst = a.partial_o + ps * kD + 4 * j;
