@@ -25,6 +25,25 @@ from paper_2602_09578_amd import inputs as I   # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes one suffix_kernel launch moves on this workload, from hardware counters
+# (profiles/decode_step_qwen7b_hbm_counters.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
+# factors a copy kernel of known size gives).  Valid only for the kernel source it was taken
+# with: reported as null when the source has changed since.
+SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5525.9e6 + 29.0e6,
+                  "attn_kernels_sha256": "ec494d28fe956530bed81cbca982aa7e8c315c42e0db420c0742edc85fa28e96"}
+
+
+def suffix_traffic(workload: str):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2602_09578_amd", "csrc", "attn_kernels.hip")
+    try:
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    if workload != SUFFIX_TRAFFIC["workload"] or digest != SUFFIX_TRAFFIC["attn_kernels_sha256"]:
+        return None
+    return SUFFIX_TRAFFIC["bytes"]
+
 
 def cpu_baseline(attn_dev: I.AttnInputs, lp_dev: I.LogprobInputs, seq_stride: int, lp_rows: int):
     """Times the float64 checker (as it stands, all host threads) on every `seq_stride`-th
@@ -110,7 +129,13 @@ def main():
     bpt = attn.kv_bytes_per_token()
     attn_ms = stage_ms["plan"] + stage_ms["prefix"] + stage_ms["suffix"] + stage_ms["merge"]
     lp_ms = stage_ms["logprob"] + stage_ms["logprob_finish"]
-    suffix_gbps = stok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
+    # the suffix kernel processes the suffix items of more than 128 tokens (the shorter ones
+    # are taken by the prefix kernel's workgroups): its algorithmic bytes per launch
+    S = attn.suffix_lens.cpu().numpy().astype(np.int64)
+    Cs = call.layout.suffix_chunk_tokens
+    tail = S % Cs
+    long_tok = int(((S // Cs) * Cs * (Cs > 128) + tail * (tail > 128)).sum())
+    suffix_gbps = long_tok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
     res = {
         "metric": "rollout decode step throughput (paged shared-prefix decode attention + token log-probs)",
         "value": w.num_seqs / (ms_per_step * 1e-3),
@@ -131,7 +156,8 @@ def main():
         "logprob_rows_per_s": w.num_seqs / (lp_ms * 1e-3),
         "logprob_GBps": w.num_seqs * vocab * 2 / (lp_ms * 1e-3) / 1e9,
         "roofline": {"kernel": "suffix_kernel", "bound": "hbm", "achieved": suffix_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": None},
+                     "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": suffix_traffic(w.name),
+                     "algorithmic_bytes_per_launch": long_tok * bpt, "avg_launch_ms": stage_ms["suffix"]},
     }
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
