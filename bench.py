@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--prefix-chunk", type=int, default=0)
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: this library has no multi-GPU path (run with --gpus 1)")
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU: the library has no CPU path")
 
@@ -159,6 +159,25 @@ def main():
                      "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": suffix_traffic(w.name),
                      "algorithmic_bytes_per_launch": long_tok * bpt, "avg_launch_ms": stage_ms["suffix"]},
     }
+    # KV append (the cache maintenance that precedes attention in a decode iteration), timed
+    # after everything else because it overwrites each sequence's last token
+    k_new = I.randn_bf16((w.num_seqs, w.Hkv, 128), 1.0, torch.Generator(device=dev).manual_seed(1), dev)
+    v_new = I.randn_bf16((w.num_seqs, w.Hkv, 128), 1.0, torch.Generator(device=dev).manual_seed(2), dev)
+    lens_before = (attn.suffix_lens - 1).clamp(min=0)
+    lens_work = lens_before.clone()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_app = 20
+    tot = 0.0
+    for it in range(n_app + 2):
+        lens_work.copy_(lens_before)
+        ev0.record()
+        B.marl_kv_append(call.shape, k_new, v_new, attn.k_pages, attn.v_pages, attn.suffix_block_table, lens_work)
+        ev1.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            tot += ev0.elapsed_time(ev1)
+    res["kv_append"] = {"us_per_call": tot / n_app * 1e3, "tokens": w.num_seqs,
+                        "bytes_written": w.num_seqs * w.Hkv * 128 * 2 * 2}
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
     print(json.dumps(res))

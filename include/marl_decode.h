@@ -158,6 +158,33 @@ int marl_attn_plan(const marl_attn_shape* shape, void* workspace, size_t workspa
 int marl_attn_read_flags(const void* workspace, int32_t* flags_host, void* stream);
 
 /*
+ * KV-cache maintenance for the decode loop (what happens before marl_decode_attn in a decode
+ * iteration).  Both are pure data movement; results are bit-exact.
+ *
+ * marl_kv_append: for every sequence s, with pos = suffix_lens[s], stores the new token's key
+ * k_new[s, kh, :] at k_pages[page, kh, pos % 16, :] and its value v_new[s, kh, c] at
+ * v_pages[page, kh, c, pos % 16], page = suffix_block_table[s][pos / 16], then sets
+ * suffix_lens[s] = pos + 1.  The caller must have put a page into the table row when pos is a
+ * multiple of 16.  A sequence whose table row is full (pos >= max_suffix_pages * 16) or whose
+ * page id is outside [0, num_pages) is left untouched (length included) and, if `flags` is not
+ * NULL, MARL_FLAG_LEN_CLAMPED / MARL_FLAG_BAD_PAGE is OR-ed into *flags (device int32).
+ * Only num_seqs, num_kv_heads, head_dim, page_size, num_pages and max_suffix_pages of the
+ * shape are used.  Device arrays: k_new, v_new bf16 [NS, Hkv, 128]; the rest as in
+ * marl_decode_attn (k_pages, v_pages and suffix_lens are written).
+ *
+ * marl_kv_copy_pages: for i < n copies physical page src[i] to page dst[i] (all KV heads, K
+ * and V), the device half of forking a sample from another one (the host allocates dst and
+ * edits the block tables).  src, dst: device int32 [n]; a dst must not appear twice or as a
+ * src of the same call.  Pairs with an id outside [0, num_pages) are skipped and flagged.
+ */
+int marl_kv_append(const marl_attn_shape* shape, const void* k_new, const void* v_new,
+                   void* k_pages, void* v_pages, const int32_t* suffix_block_table,
+                   int32_t* suffix_lens, int32_t* flags, void* stream);
+int marl_kv_copy_pages(const marl_attn_shape* shape, void* k_pages, void* v_pages,
+                       const int32_t* src, const int32_t* dst, int32_t n, int32_t* flags,
+                       void* stream);
+
+/*
  * Per-row log-probability of one chosen token:
  *   out[r] = logits[r, tokens[r]] / T - log( sum_v exp(logits[r, v] / T) )
  * Device arrays: logits bf16 [rows, vocab] (row stride = vocab elements), tokens int32

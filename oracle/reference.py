@@ -157,3 +157,51 @@ def merge_summaries(parts):
 def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
     """Exact widening of bf16 bit patterns (uint16) to float64."""
     return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+# ------------------------------------------------------------------------------------------
+# KV-cache maintenance of the decode loop, as plain scatter / copy on the ABI layouts
+# (K [page][kv_head][slot][128], V [page][kv_head][128][slot]).  The paper says only that rollout
+# manages large KV caches (Section 4.1); these are the definitions written in the library header.
+# ------------------------------------------------------------------------------------------
+def kv_append(k_pages, v_pages, suffix_table, suffix_lens, k_new, v_new):
+    """Appends one token per sequence.  Arrays of bf16 bit patterns (uint16): k_pages
+    [num_pages, Hkv, 16, 128], v_pages [num_pages, Hkv, 128, 16], k_new / v_new [NS, Hkv, 128].
+    Returns (k_pages, v_pages, suffix_lens, flags) as new arrays; a sequence whose table row is
+    full (flag 2) or whose page id is out of range (flag 4) is left untouched."""
+    k_pages, v_pages = k_pages.copy(), v_pages.copy()
+    lens = np.array(suffix_lens, dtype=np.int32).copy()
+    table = np.asarray(suffix_table, dtype=np.int32)
+    num_pages = k_pages.shape[0]
+    flags = 0
+    for s in range(lens.shape[0]):
+        pos = int(lens[s])
+        if pos < 0 or pos >= table.shape[1] * 16:
+            flags |= 2
+            continue
+        page = int(table[s, pos // 16])
+        if page < 0 or page >= num_pages:
+            flags |= 4
+            continue
+        slot = pos % 16
+        for kh in range(k_pages.shape[1]):
+            for c in range(128):
+                k_pages[page, kh, slot, c] = k_new[s, kh, c]
+                v_pages[page, kh, c, slot] = v_new[s, kh, c]
+        lens[s] = pos + 1
+    return k_pages, v_pages, lens, flags
+
+
+def kv_copy_pages(k_pages, v_pages, src, dst):
+    """dst[i] <- src[i], whole pages of K and V; pairs with an id out of range are skipped
+    (flag 4).  Returns (k_pages, v_pages, flags)."""
+    k_pages, v_pages = k_pages.copy(), v_pages.copy()
+    n = k_pages.shape[0]
+    flags = 0
+    for a, b in zip(np.asarray(src).tolist(), np.asarray(dst).tolist()):
+        if not (0 <= a < n and 0 <= b < n):
+            flags |= 4
+            continue
+        k_pages[b] = k_pages[a]
+        v_pages[b] = v_pages[a]
+    return k_pages, v_pages, flags

@@ -72,6 +72,9 @@ def load_library(build_if_missing: bool = True):
     lib.marl_attn_read_flags.argtypes = [VP, ctypes.POINTER(I32), VP]
     lib.marl_logprobs_workspace_bytes.argtypes = [I32, I32, ctypes.POINTER(SZ)]
     lib.marl_token_logprobs.argtypes = [VP, VP, ctypes.c_float, VP, I32, I32, VP, SZ, VP]
+    lib.marl_kv_append.argtypes = [PS, VP, VP, VP, VP, VP, VP, VP, VP]
+    lib.marl_kv_copy_pages.argtypes = [PS, VP, VP, VP, VP, I32, VP, VP]
+    lib.marl_kv_append.restype = lib.marl_kv_copy_pages.restype = ctypes.c_int
     lib.marl_profile_begin.argtypes = [I32]
     lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
     for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_attn_plan",
@@ -175,6 +178,22 @@ def marl_token_logprobs(logits: torch.Tensor, tokens: torch.Tensor, temperature:
         0 if workspace is None else workspace.numel(), _stream(logits.device))
     _check(rc, "marl_token_logprobs")
     return out
+
+
+def marl_kv_append(shape: AttnShape, k_new, v_new, k_pages, v_pages, suffix_block_table, suffix_lens,
+                   flags: Optional[torch.Tensor] = None):
+    _require_cuda(k_new, v_new, k_pages, v_pages, suffix_block_table, suffix_lens, flags)
+    rc = load_library().marl_kv_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_pages), _ptr(v_pages),
+                                       _ptr(suffix_block_table), _ptr(suffix_lens), _ptr(flags),
+                                       _stream(k_pages.device))
+    _check(rc, "marl_kv_append")
+
+
+def marl_kv_copy_pages(shape: AttnShape, k_pages, v_pages, src, dst, flags: Optional[torch.Tensor] = None):
+    _require_cuda(k_pages, v_pages, src, dst, flags)
+    rc = load_library().marl_kv_copy_pages(ctypes.byref(shape), _ptr(k_pages), _ptr(v_pages), _ptr(src), _ptr(dst),
+                                           int(src.numel()), _ptr(flags), _stream(k_pages.device))
+    _check(rc, "marl_kv_copy_pages")
 
 
 def marl_profile_begin(max_calls: int):

@@ -280,6 +280,52 @@ int marl_attn_read_flags(const void* workspace, int32_t* flags_host, void* strea
   return e == hipSuccess ? MARL_OK : hip_fail(e, "read flags");
 }
 
+// ---- KV-cache maintenance ---------------------------------------------------------------------
+int marl_kv_append(const marl_attn_shape* shape, const void* k_new, const void* v_new,
+                   void* k_pages, void* v_pages, const int32_t* suffix_block_table,
+                   int32_t* suffix_lens, int32_t* flags, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != MARL_OK) return rc;
+  if (shape->num_seqs == 0) return MARL_OK;
+  if (!k_new || !v_new || !k_pages || !v_pages || !suffix_block_table || !suffix_lens) return MARL_INVALID_ARG;
+  if (shape->max_suffix_pages < 1) return MARL_INVALID_ARG;
+  marl::KvAppendArgs a;
+  a.k_new = static_cast<const uint16_t*>(k_new);
+  a.v_new = static_cast<const uint16_t*>(v_new);
+  a.k_pages = static_cast<uint16_t*>(k_pages);
+  a.v_pages = static_cast<uint16_t*>(v_pages);
+  a.suffix_table = suffix_block_table;
+  a.suffix_lens = suffix_lens;
+  a.flags = flags;
+  a.NS = shape->num_seqs;
+  a.Hkv = shape->num_kv_heads;
+  a.num_pages = shape->num_pages;
+  a.max_sp = shape->max_suffix_pages;
+  const hipError_t e = marl::launch_kv_append(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "kv append kernel");
+}
+
+int marl_kv_copy_pages(const marl_attn_shape* shape, void* k_pages, void* v_pages,
+                       const int32_t* src, const int32_t* dst, int32_t n, int32_t* flags,
+                       void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != MARL_OK) return rc;
+  if (n < 0 || n >= (1 << 30)) return MARL_INVALID_ARG;
+  if (n == 0) return MARL_OK;
+  if (!k_pages || !v_pages || !src || !dst) return MARL_INVALID_ARG;
+  marl::KvCopyArgs a;
+  a.k_pages = static_cast<uint16_t*>(k_pages);
+  a.v_pages = static_cast<uint16_t*>(v_pages);
+  a.src = src;
+  a.dst = dst;
+  a.flags = flags;
+  a.n = n;
+  a.Hkv = shape->num_kv_heads;
+  a.num_pages = shape->num_pages;
+  const hipError_t e = marl::launch_kv_copy_pages(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "kv copy kernel");
+}
+
 // ---- log-probabilities ------------------------------------------------------------------------
 static int logprob_split(int32_t rows, int32_t vocab, int32_t* slices, int32_t* slice_len) {
   if (rows < 0 || vocab < 1) return MARL_INVALID_ARG;

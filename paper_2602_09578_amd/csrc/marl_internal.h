@@ -60,6 +60,27 @@ hipError_t launch_merge(const AttnArgs& a, hipStream_t st);
 int prefix_blocks_per_cu();
 int suffix_blocks_per_cu();
 
+struct KvAppendArgs {
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  uint16_t* k_pages;
+  uint16_t* v_pages;
+  const int32_t* suffix_table;
+  int32_t* suffix_lens;
+  int32_t* flags;   // may be null
+  int32_t NS, Hkv, num_pages, max_sp;
+};
+struct KvCopyArgs {
+  uint16_t* k_pages;
+  uint16_t* v_pages;
+  const int32_t* src;
+  const int32_t* dst;
+  int32_t* flags;   // may be null
+  int32_t n, Hkv, num_pages;
+};
+hipError_t launch_kv_append(const KvAppendArgs& a, hipStream_t st);
+hipError_t launch_kv_copy_pages(const KvCopyArgs& a, hipStream_t st);
+
 struct LogprobArgs {
   const uint16_t* logits;
   const int32_t* tokens;
