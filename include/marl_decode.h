@@ -65,7 +65,8 @@ typedef struct marl_attn_plan_layout {
   int32_t prefix_chunk_tokens;   /* Cp actually used */
   int32_t suffix_slots;          /* NCs = max(1, ceil(max_suffix_pages*16 / Cs)) */
   int32_t prefix_slots;          /* NCp = max(1, ceil(max_prefix_pages*16 / Cp)) */
-  int32_t rows_per_qblock;       /* query rows one prefix work item covers (128) */
+  int32_t rows_per_qblock;       /* query rows one prefix work item covers: 256 if the average
+                                    group, ceil(NS/NG)*(Hq/Hkv) rows, exceeds 128, else 128 */
   int32_t max_suffix_items;      /* NS * NCs */
   int32_t max_prefix_items;      /* (NG + NS*(Hq/Hkv)/rows_per_qblock + 1) * NCp */
   int32_t reserved;
@@ -101,9 +102,9 @@ enum {
 /* Fills *layout for *shape.  Host-only, no GPU needed.
  * Chunking rule when the shape gives 0:  Cs starts at 8192 and is halved while
  * NS*Hkv*ceil(max_suffix_tokens/Cs) < 2048 and Cs > 256;  Cp starts at 8192 and is halved
- * while NG*Hkv*Q*ceil(max_prefix_tokens/Cp) < 512 and Cp > 256, where
+ * while NG*Hkv*Q*ceil(max_prefix_tokens/Cp) < W and Cp > 256, where
  * Q = max(1, ceil(ceil(NS/NG)*(Hq/Hkv) / rows_per_qblock)) estimates the query-row blocks of
- * a group. */
+ * a group and W = 512 (256 when rows_per_qblock is 256). */
 int marl_attn_plan_layout_for(const marl_attn_shape* shape, marl_attn_plan_layout* layout);
 
 /* *bytes = layout.total_bytes (an upper bound that depends on the shape only). Host-only. */

@@ -15,12 +15,18 @@ from typing import List, Tuple
 import numpy as np
 
 PAGE = 16
-ROWS_PER_QBLOCK = 128
+ROWS_PER_QBLOCK = 128          # query rows of a prefix work item ...
+ROWS_PER_QBLOCK_WIDE = 256     # ... when the average group has more than 128 query rows
 SHORT_TOKENS = 128     # suffix items above this many tokens head the list
 
 
 def _ceil_div(a: int, b: int) -> int:
     return -(-a // b)
+
+
+def rows_per_qblock(NS: int, NG: int, Hq: int, Hkv: int) -> int:
+    rows = _ceil_div(NS, NG) * (Hq // Hkv) if NG > 0 else 0
+    return ROWS_PER_QBLOCK_WIDE if rows > ROWS_PER_QBLOCK else ROWS_PER_QBLOCK
 
 
 def default_chunks(NS: int, NG: int, Hq: int, Hkv: int, max_prefix_pages: int, max_suffix_pages: int,
@@ -33,10 +39,12 @@ def default_chunks(NS: int, NG: int, Hq: int, Hkv: int, max_prefix_pages: int, m
             Cs //= 2
     Cp = prefix_chunk
     if Cp == 0:
+        qb = rows_per_qblock(NS, NG, Hq, Hkv)
         rows = _ceil_div(NS, NG) * (Hq // Hkv) if NG > 0 else 0
-        qblocks = max(1, _ceil_div(rows, ROWS_PER_QBLOCK))
+        qblocks = max(1, _ceil_div(rows, qb))
         Cp = 8192
-        while NG * Hkv * qblocks * _ceil_div(mpt, Cp) < 512 and Cp > 256:
+        want = 256 if qb == ROWS_PER_QBLOCK_WIDE else 512
+        while NG * Hkv * qblocks * _ceil_div(mpt, Cp) < want and Cp > 256:
             Cp //= 2
     return Cs, Cp
 
@@ -67,6 +75,7 @@ def build_plan(prefix_lens, suffix_lens, group_of_seq, Hq: int, Hkv: int, max_pr
     gos = np.asarray(group_of_seq, dtype=np.int64)
     NS, NG = len(sl), len(pl)
     R = Hq // Hkv
+    QB = rows_per_qblock(NS, NG, Hq, Hkv)
     Cs, Cp = default_chunks(NS, NG, Hq, Hkv, max_prefix_pages, max_suffix_pages, suffix_chunk, prefix_chunk)
     mst, mpt = max_suffix_pages * PAGE, max_prefix_pages * PAGE
     flags = 0
@@ -101,7 +110,7 @@ def build_plan(prefix_lens, suffix_lens, group_of_seq, Hq: int, Hkv: int, max_pr
         P = clamp(pl[g], mpt)
         rows = int(count[g]) * R
         for t0 in range(0, P, Cp):
-            for r0 in range(0, rows, ROWS_PER_QBLOCK):
+            for r0 in range(0, rows, QB):
                 pitems.append((g, t0, min(P, t0 + Cp), r0))
     chunks = np.zeros(NS, dtype=np.int32)
     for s in range(NS):

@@ -48,6 +48,10 @@ int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
   memset(L, 0, sizeof *L);
   const long NS = s->num_seqs, NG = s->num_groups, Hkv = s->num_kv_heads, Hq = s->num_q_heads;
   const long mst = (long)s->max_suffix_pages * marl::kPage, mpt = (long)s->max_prefix_pages * marl::kPage;
+  // Groups with more than 128 query rows (judged by the average group) use the 8-wave prefix
+  // kernel with blocks of 256 rows, so that their prefix KV is streamed once, not twice.
+  const long rows = NG > 0 ? ceil_div(NS, NG) * (Hq / Hkv) : 0;   // query rows of an average group
+  const long qb = rows > marl::kRowsPerQBlock ? marl::kRowsPerQBlockWide : marl::kRowsPerQBlock;
   // Default chunks: as large as possible (every work item costs a fixed few microseconds and
   // one partial per query row) while the shape still promises enough items to fill the GPU.
   long Cs = s->suffix_chunk_tokens;
@@ -57,23 +61,23 @@ int make_layout(const marl_attn_shape* s, marl_attn_plan_layout* L) {
   }
   long Cp = s->prefix_chunk_tokens;
   if (Cp == 0) {
-    const long rows = NG > 0 ? ceil_div(NS, NG) * (Hq / Hkv) : 0;   // query rows of an average group
-    const long qblocks = rows > marl::kRowsPerQBlock ? ceil_div(rows, marl::kRowsPerQBlock) : 1;
+    const long qblocks = rows > qb ? ceil_div(rows, qb) : 1;
     Cp = 8192;
-    while (NG * Hkv * qblocks * ceil_div(mpt, Cp) < 512 && Cp > 256) Cp /= 2;
+    const long want = qb == marl::kRowsPerQBlockWide ? 256 : 512;   // about one item per resident workgroup
+    while (NG * Hkv * qblocks * ceil_div(mpt, Cp) < want && Cp > 256) Cp /= 2;
   }
   const long NCs = ceil_div(mst, Cs) > 1 ? ceil_div(mst, Cs) : 1;
   const long NCp = ceil_div(mpt, Cp) > 1 ? ceil_div(mpt, Cp) : 1;
   const long R = Hq / Hkv;
   const long max_s_items = NS * NCs;
-  const long max_p_items = (NG + NS * R / marl::kRowsPerQBlock + 1) * NCp;
+  const long max_p_items = (NG + NS * R / qb + 1) * NCp;
   if (max_s_items >= (1L << 28) || max_p_items >= (1L << 28)) return MARL_UNSUPPORTED;
   if (NCs >= (1L << 15) || NCp >= (1L << 15)) return MARL_UNSUPPORTED;   // packed into 16 bits each
   L->suffix_chunk_tokens = (int32_t)Cs;
   L->prefix_chunk_tokens = (int32_t)Cp;
   L->suffix_slots = (int32_t)NCs;
   L->prefix_slots = (int32_t)NCp;
-  L->rows_per_qblock = marl::kRowsPerQBlock;
+  L->rows_per_qblock = (int32_t)qb;
   L->max_suffix_items = (int32_t)max_s_items;
   L->max_prefix_items = (int32_t)max_p_items;
   size_t off = 0;
@@ -120,7 +124,7 @@ struct StageTimer {
   }
 };
 
-int g_num_cus = 0, g_prefix_bpc = 0, g_suffix_bpc = 0;
+int g_num_cus = 0, g_prefix_bpc = 0, g_prefix_wide_bpc = 0, g_suffix_bpc = 0;
 
 std::once_flag g_dev_once;
 hipError_t g_dev_err = hipSuccess;
@@ -133,7 +137,8 @@ void query_device() {
   g_dev_err = hipGetDeviceProperties(&p, dev);
   if (g_dev_err != hipSuccess) return;
   g_num_cus = p.multiProcessorCount;
-  g_prefix_bpc = marl::prefix_blocks_per_cu();
+  g_prefix_bpc = marl::prefix_blocks_per_cu(false);
+  g_prefix_wide_bpc = marl::prefix_blocks_per_cu(true);
   g_suffix_bpc = marl::suffix_blocks_per_cu();
 }
 
@@ -169,6 +174,7 @@ int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArg
   a.Cp = L.prefix_chunk_tokens;
   a.NCs = L.suffix_slots;
   a.NCp = L.prefix_slots;
+  a.qblock_rows = L.rows_per_qblock;
   a.out_dtype = s->out_dtype;
   return MARL_OK;
 }
@@ -259,7 +265,7 @@ int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t works
   if ((e = T.run(MARL_STAGE_PLAN, [&] { return marl::launch_plan(a, st); })) != hipSuccess)
     return hip_fail(e, "plan kernel");
   {  // always launched: its workgroups also process the short suffix items
-    if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * g_prefix_bpc, st); })) != hipSuccess)
+    if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * (a.qblock_rows == marl::kRowsPerQBlockWide ? g_prefix_wide_bpc : g_prefix_bpc), st); })) != hipSuccess)
       return hip_fail(e, "prefix kernel");
   }
   if (a.max_sp > 0) {

@@ -391,18 +391,19 @@ void suffix_kernel(AttnArgs a) {
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }
 
-__device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_rec)[2][kWaves], int (&s_idx)[2], int& bad_page) {
+template <int NW>
+__device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_rec)[2][NW], int (&s_idx)[2], int& bad_page) {
   const int tid = threadIdx.x;
   const int n_long = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
   const int n_work = a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] * a.Hkv;
   if (n_long >= n_work) return;
   const int i = tid & 15;
   const int wave = tid >> 6;
-  if (tid < kWaves) {
+  if (tid < NW) {
     int i0 = 0, i1 = 0;
     if (tid == 0) {
-      i0 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], kWaves);
-      i1 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], kWaves);
+      i0 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], NW);
+      i1 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], NW);
       s_idx[0] = i0;
       s_idx[1] = i1;
     }
@@ -418,10 +419,10 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_r
     __syncthreads();   // everybody has read this round's slots before they are refilled
     int inew = 0;
     int4 nrec = make_int4(0, 0, 0, 0);
-    if (tid < kWaves) {
+    if (tid < NW) {
       const int inext = s_idx[b ^ 1] + tid;
       if (inext < n_work) nrec = a.suffix_items[inext / a.Hkv];
-      if (tid == 0) inew = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], kWaves);
+      if (tid == 0) inew = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], NW);
     }
     if (qi < n_work) {   // wave-uniform
       const int kvh = qi % a.Hkv;
@@ -431,7 +432,7 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_r
       process_item<1, 1>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
                          a.NCp + it.y / a.Cs, *no_lds, bad_page);
     }
-    if (tid < kWaves) {
+    if (tid < NW) {
       s_rec[b ^ 1][tid] = nrec;
       if (tid == 0) s_idx[b] = inew;
     }
@@ -440,11 +441,11 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_r
 }
 
 // ---------------------------------------------------------------------------------------
-// Prefix kernel: one work item = (group, chunk of prefix tokens, block of up to 128 query
-// rows, KV head).  Query row rho of a group is (its rho / R -th sequence, head kvh*R + rho % R).
+// Prefix kernel: one work item = (group, chunk of prefix tokens, block of up to 128 (or 256)
+// query rows, KV head).  Query row rho of a group is (its rho / R -th sequence, head kvh*R + rho % R).
 //
-// Here the four waves split the QUERY rows (16-row tile t belongs to wave t % 4) and every
-// wave sees all tokens, so the group's K/V must reach all four: each 32-token step (two
+// Here the NW (4 or 8) waves split the QUERY rows (16-row tile t belongs to wave t % NW) and
+// every wave sees all tokens, so the group's K/V must reach all of them: each 32-token step (two
 // pages, 16 KB of K and V) is fetched once by the workgroup with fully coalesced 16-byte
 // loads (a wave reads 1 KB contiguous per instruction), staged in registers, written to a
 // triple-buffered LDS tile and read back in MFMA operand layout.  Loads run three steps
@@ -460,9 +461,11 @@ struct PrefixLds {
   __attribute__((aligned(16))) char buf[3][kStepBytes];
 };
 
-template <int MTW>
+template <int MTW, int NW>
 __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, const int kvh,
                                             PrefixLds& lds, int& bad_page) {
+  constexpr int kQBlock = 32 * NW;              // query rows of one item: two 16-row tiles per wave
+  constexpr int kLoads = 1024 / (NW * 64);      // 16-byte loads per thread and step (16 KB per step)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -477,15 +480,15 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   const int slot = tok_begin / a.Cp;
 
   // this wave's tiles: wave, wave + 4, ...; nt of them hold at least one real row
-  const int tiles_total = (min(kRowsPerQBlock, nrows - row_begin) + 15) >> 4;
-  const int nt = max(0, min(MTW, (tiles_total - wave + kWaves - 1) / kWaves));   // wave-uniform
+  const int tiles_total = (min(kQBlock, nrows - row_begin) + 15) >> 4;
+  const int nt = max(0, min(MTW, (tiles_total - wave + NW - 1) / NW));   // wave-uniform
   int row_index[MTW];
   u32x4 qreg[MTW][4];
 #pragma unroll
   for (int qt = 0; qt < MTW; ++qt) {
-    const int rho = row_begin + (qt * kWaves + wave) * 16 + i;
+    const int rho = row_begin + (qt * NW + wave) * 16 + i;
     int idx = -1;
-    if (rho < nrows && (qt * kWaves + wave) * 16 < kRowsPerQBlock)
+    if (rho < nrows && (qt * NW + wave) * 16 < kQBlock)
       idx = a.group_seqs[gstart + rho / a.R] * a.Hq + kvh * a.R + rho % a.R;
     row_index[qt] = idx;
 #pragma unroll
@@ -510,8 +513,6 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
 
   const int nsteps = (tok_end - tok_begin + kBlockTok - 1) / kBlockTok;
   const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
-  const char* kbase = reinterpret_cast<const char*>(a.k_pages) + (size_t)kvh * (kPage * kD * 2) + tid * 16;
-  const char* vbase = reinterpret_cast<const char*>(a.v_pages) + (size_t)kvh * (kPage * kD * 2) + tid * 16;
   const char* dummy = reinterpret_cast<const char*>(a.q);   // any valid 16 bytes
 
   // Page ids of step n (wave-uniform scalar loads); steps past the end yield -1.
@@ -526,24 +527,35 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
       if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
     }
   };
+  // A step is 1024 16-byte vectors: K of page 0, K of page 1, V of page 0, V of page 1 (256
+  // each, contiguous in memory).  Thread tid fetches vectors tid + k * (threads), k < kLoads.
+  // Of a page's 256 vectors, vector w is slot w/16, chunk w%16 of K, or 16-byte unit w of V.
+  const char* src_base[kLoads];
+  int lds_off[kLoads];
+  bool second_page[kLoads];
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    const int v = tid + k * NW * 64;
+    const int region = v >> 8, w = v & 255;
+    second_page[k] = region & 1;
+    const bool is_v = region >> 1;
+    src_base[k] = reinterpret_cast<const char*>(is_v ? a.v_pages : a.k_pages) + (size_t)kvh * (kPage * kD * 2) + w * 16;
+    // K rows of page 1 are tau = 16 + slot: the swizzle key (tau&3)|((tau>>1)&4) is that of slot
+    const int slot = w >> 4;
+    lds_off[k] = is_v ? 2 * kBlockTok * kD + (region & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
+                      : ((region & 1) * 16 + slot) * 256 + (((w & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)) << 4);
+  }
   // The loads are unconditional (a step past the end re-reads 16 valid bytes that are never
   // used) so that every wait in the loop knows exactly how many younger loads are in flight.
-  auto issue = [&](int p0, int p1, u32x4 (&st)[4]) {
+  auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
     const bool ok = p0 >= 0;
-    st[0] = ld_stream(ok ? kbase + (size_t)p0 * page_bytes : dummy);
-    st[1] = ld_stream(ok ? kbase + (size_t)p1 * page_bytes : dummy);
-    st[2] = ld_stream(ok ? vbase + (size_t)p0 * page_bytes : dummy);
-    st[3] = ld_stream(ok ? vbase + (size_t)p1 * page_bytes : dummy);
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k)
+      st[k] = ld_stream(ok ? src_base[k] + (size_t)(second_page[k] ? p1 : p0) * page_bytes : dummy);
   };
-  // thread tid holds, of each page, slot tid/16, chunk tid%16 of K and 16-byte unit tid of V
-  const int k_wr = (tid >> 4) * 256 + (((tid & 15) ^ ((tid >> 4) & 3) ^ (((tid >> 4) >> 1) & 4)) << 4);
-  const int v_wr = 2 * kBlockTok * kD + ((tid ^ ((tid >> 3) & 1)) << 4);
-  auto stage_to_lds = [&](const u32x4 (&st)[4], char* buf) {
-    // K rows of page 1 are tau = 16 + slot: (tau&3)|((tau>>1)&4) is the same as for page 0
-    *reinterpret_cast<u32x4*>(buf + k_wr) = st[0];
-    *reinterpret_cast<u32x4*>(buf + 16 * 256 + k_wr) = st[1];
-    *reinterpret_cast<u32x4*>(buf + v_wr) = st[2];
-    *reinterpret_cast<u32x4*>(buf + 4096 + v_wr) = st[3];
+  auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) *reinterpret_cast<u32x4*>(buf + lds_off[k]) = st[k];
   };
   // operand reads: K row tau = 8*(i/4) + 4T + i%4, whose swizzle key is i & 7
   const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
@@ -626,7 +638,7 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   // Three register stages and three LDS buffers: while step n is computed from buffer n%3,
   // the loads of steps n+1, n+2 and n+3 are in flight (48 KB per workgroup); step n+1 moves
   // from its registers to buffer (n+1)%3 at the end of the iteration, one barrier per step.
-  u32x4 st0[4], st1[4], st2[4];
+  u32x4 st0[kLoads], st1[kLoads], st2[kLoads];
   int p0, p1;
   load_ids(0, p0, p1);
   issue(p0, p1, st0);
@@ -674,22 +686,18 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   }
 }
 
-#ifndef MARL_PREFIX_WAVES_PER_EU
-#define MARL_PREFIX_WAVES_PER_EU 2
-#endif
-__global__ __launch_bounds__(kAttnThreads)
-__attribute__((amdgpu_waves_per_eu(MARL_PREFIX_WAVES_PER_EU, MARL_PREFIX_WAVES_PER_EU)))
-void prefix_kernel(AttnArgs a) {
+template <int NW>
+__device__ __forceinline__ void prefix_kernel_body(const AttnArgs& a) {
   __shared__ PrefixLds lds;
   __shared__ int next_item;
-  __shared__ int s_idx[2];             // short suffix items: first queue index of this / the next round
-  __shared__ int4 s_rec[2][kWaves];    // and their item records
+  __shared__ int s_idx[2];          // short suffix items: first queue index of this / the next round
+  __shared__ int4 s_rec[2][NW];     // and their item records
   const int n_work = a.counters[MARL_CTR_NUM_PREFIX_ITEMS] * a.Hkv;
   int bad_page = 0;
   // The short suffix items go first: each round is a chain of dependent memory accesses with
   // little data, which is cheap while every workgroup has other work to overlap it with and
   // expensive at the tail of a kernel, where only a few workgroups are left.
-  short_suffix_items(a, s_rec, s_idx, bad_page);
+  short_suffix_items<NW>(a, s_rec, s_idx, bad_page);
   __syncthreads();
   for (;;) {
     if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_PREFIX_CURSOR], 1);
@@ -699,18 +707,28 @@ void prefix_kernel(AttnArgs a) {
     if (qi >= n_work) break;
     const int4 it = a.prefix_items[qi / a.Hkv];
     const int kvh = qi % a.Hkv;
-    const int rows = min(kRowsPerQBlock, a.group_count[it.x] * a.R - it.w);
-    if (kRowsPerQBlock <= 16 * kWaves || rows <= 16 * kWaves) prefix_item<1>(a, it, kvh, lds, bad_page);   // workgroup-uniform
-    else prefix_item<2>(a, it, kvh, lds, bad_page);
+    const int rows = min(32 * NW, a.group_count[it.x] * a.R - it.w);
+    if (rows <= 16 * NW) prefix_item<1, NW>(a, it, kvh, lds, bad_page);   // workgroup-uniform
+    else prefix_item<2, NW>(a, it, kvh, lds, bad_page);
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }
 
+// Two shapes of the same kernel: 4 waves and blocks of 128 query rows (two workgroups per CU),
+// or 8 waves and blocks of 256 rows (one workgroup per CU) for groups with more than 128 rows,
+// whose prefix KV would otherwise be streamed once per 128-row block.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void prefix_kernel(AttnArgs a) { prefix_kernel_body<4>(a); }
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void prefix_kernel_wide(AttnArgs a) { prefix_kernel_body<8>(a); }
+
 }  // namespace
 
-int prefix_blocks_per_cu() {
+int prefix_blocks_per_cu(bool wide) {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, prefix_kernel, kAttnThreads, 0) != hipSuccess || n < 1) n = 1;
+  const hipError_t e = wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, prefix_kernel_wide, 512, 0)
+                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, prefix_kernel, 256, 0);
+  if (e != hipSuccess || n < 1) n = 1;
   return n;
 }
 int suffix_blocks_per_cu() {
@@ -720,7 +738,8 @@ int suffix_blocks_per_cu() {
 }
 
 hipError_t launch_prefix(const AttnArgs& a, int grid, hipStream_t st) {
-  hipLaunchKernelGGL(prefix_kernel, dim3(grid), dim3(kAttnThreads), 0, st, a);
+  if (a.qblock_rows == 256) hipLaunchKernelGGL(prefix_kernel_wide, dim3(grid), dim3(512), 0, st, a);
+  else hipLaunchKernelGGL(prefix_kernel, dim3(grid), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st) {

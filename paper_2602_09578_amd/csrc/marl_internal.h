@@ -10,11 +10,8 @@ namespace marl {
 constexpr int kPage = 16;        // tokens per page
 constexpr int kD = 128;          // head dimension
 constexpr int kBlockTok = 32;    // tokens one MFMA step of a wave covers (two pages)
-// query rows one prefix work item covers: 64 (one 16-row tile per wave) or 128 (two)
-#ifndef MARL_ROWS_PER_QBLOCK
-#define MARL_ROWS_PER_QBLOCK 128
-#endif
-constexpr int kRowsPerQBlock = MARL_ROWS_PER_QBLOCK;
+constexpr int kRowsPerQBlock = 128;       // query rows one prefix work item covers (4-wave kernel)
+constexpr int kRowsPerQBlockWide = 256;   // ... in the 8-wave kernel
 // suffix items up to this many tokens are handled by one wave (build-time tuning knob)
 #ifndef MARL_SHORT_TOKENS
 #define MARL_SHORT_TOKENS 128
@@ -49,6 +46,7 @@ struct AttnArgs {
   int32_t NS, NG, Hq, Hkv, R;
   int32_t num_pages, max_pp, max_sp;
   int32_t Cs, Cp, NCs, NCp;
+  int32_t qblock_rows;   // kRowsPerQBlock or kRowsPerQBlockWide
   int32_t out_dtype;
   float scale;
 };
@@ -57,7 +55,7 @@ hipError_t launch_plan(const AttnArgs& a, hipStream_t st);
 hipError_t launch_prefix(const AttnArgs& a, int grid, hipStream_t st);
 hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st);
 hipError_t launch_merge(const AttnArgs& a, hipStream_t st);
-int prefix_blocks_per_cu();
+int prefix_blocks_per_cu(bool wide);
 int suffix_blocks_per_cu();
 
 struct KvAppendArgs {

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   __shared__ int tmp[17];
   __shared__ int n_long_items;
   const int tid = threadIdx.x;
-  const int Cs = a.Cs, Cp = a.Cp, R = a.R;
+  const int Cs = a.Cs, Cp = a.Cp, R = a.R, QB = a.qblock_rows;
   const int ncls_s = Cs / 32, ncls_p = Cp / 32;
   const int max_st = a.max_sp * kPage, max_pt = a.max_pp * kPage;
   int flags = 0;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   // groups: histogram of prefix items (one per chunk and per block of query rows)
   for (int g = tid; g < a.NG; g += kPlanThreads) {
     const int P = clamp_len(a.prefix_lens[g], max_pt, flags);
-    const int nqb = (ld_agent(a.group_count + g) * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+    const int nqb = (ld_agent(a.group_count + g) * R + QB - 1) / QB;
     const int nfull = P / Cp, tail = P % Cp;
     if (nqb) {
       if (nfull) atomicAdd(&hist_p[0], nfull * nqb);
@@ -142,19 +142,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   for (int g = tid; g < a.NG; g += kPlanThreads) {
     int dummy = 0;
     const int P = clamp_len(a.prefix_lens[g], max_pt, dummy);
-    const int nqb = (ld_agent(a.group_count + g) * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+    const int nqb = (ld_agent(a.group_count + g) * R + QB - 1) / QB;
     const int nfull = P / Cp, tail = P % Cp;
     if (nqb) {
       if (nfull) {
         const int pos = atomicAdd(&hist_p[0], nfull * nqb);
         for (int i = 0; i < nfull; ++i)
           for (int b = 0; b < nqb; ++b)
-            a.prefix_items[pos + i * nqb + b] = make_int4(g, i * Cp, (i + 1) * Cp, b * kRowsPerQBlock);
+            a.prefix_items[pos + i * nqb + b] = make_int4(g, i * Cp, (i + 1) * Cp, b * QB);
       }
       if (tail) {
         const int pos = atomicAdd(&hist_p[(Cp - tail) / 32], nqb);
         for (int b = 0; b < nqb; ++b)
-          a.prefix_items[pos + b] = make_int4(g, nfull * Cp, P, b * kRowsPerQBlock);
+          a.prefix_items[pos + b] = make_int4(g, nfull * Cp, P, b * QB);
       }
     }
   }
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
   __shared__ int tmp[17];
   __shared__ int n_long_items;
   const int tid = threadIdx.x;
-  const int Cs = a.Cs, Cp = a.Cp, R = a.R;
+  const int Cs = a.Cs, Cp = a.Cp, R = a.R, QB = a.qblock_rows;
   const int ncls_s = Cs / 32, ncls_p = Cp / 32;
   const int max_st = a.max_sp * kPage, max_pt = a.max_pp * kPage;
   int flags = 0;
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
     const int g = tid + k * kPlanThreads;
     if (g < a.NG) {
       P_of[k] = clamp_len(P_of[k], max_pt, flags);
-      const int nqb = (cnt[g] * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+      const int nqb = (cnt[g] * R + QB - 1) / QB;
       const int nfull = P_of[k] / Cp, tail = P_of[k] % Cp;
       if (nqb) {
         if (nfull) atomicAdd(&hist_p[0], nfull * nqb);
@@ -299,19 +299,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
       a.group_count[g] = cnt[g];
       a.group_start[g] = start[g];
       const int P = P_of[k];
-      const int nqb = (cnt[g] * R + kRowsPerQBlock - 1) / kRowsPerQBlock;
+      const int nqb = (cnt[g] * R + QB - 1) / QB;
       const int nfull = P / Cp, tail = P % Cp;
       if (nqb) {
         if (nfull) {
           const int pos = atomicAdd(&hist_p[0], nfull * nqb);
           for (int i = 0; i < nfull; ++i)
             for (int b = 0; b < nqb; ++b)
-              a.prefix_items[pos + i * nqb + b] = make_int4(g, i * Cp, (i + 1) * Cp, b * kRowsPerQBlock);
+              a.prefix_items[pos + i * nqb + b] = make_int4(g, i * Cp, (i + 1) * Cp, b * QB);
         }
         if (tail) {
           const int pos = atomicAdd(&hist_p[(Cp - tail) / 32], nqb);
           for (int b = 0; b < nqb; ++b)
-            a.prefix_items[pos + b] = make_int4(g, nfull * Cp, P, b * kRowsPerQBlock);
+            a.prefix_items[pos + b] = make_int4(g, nfull * Cp, P, b * QB);
         }
       }
     }

@@ -78,12 +78,17 @@ def test_head_layouts(Hq, Hkv):
     check_attn(inp, B.MARL_OUT_F32)
 
 
-def test_big_group_many_query_blocks():
-    """A group whose G*R rows need several 64-row blocks, the last one ragged."""
-    print("case: big group", flush=True)
-    G = 21                      # 21 * 7 = 147 rows -> blocks of 64, 64, 19
-    inp = custom_inputs([200], list(range(1, G + 1)), [0] * G, 28, 4, seed=9)
+@pytest.mark.parametrize("sizes", [[21], [40], [60, 2], [17, 19, 1]])
+def test_big_groups_and_query_row_blocks(sizes):
+    """Groups whose G*R query rows fill one ragged block or several blocks of the prefix
+    kernel: 147 rows (8-wave kernel, one block), 280 rows (two blocks of 256), a large and a
+    tiny group together (8-wave kernel), groups just under and over 128 rows (4-wave kernel)."""
+    print("case: big groups", sizes, flush=True)
+    gos = np.repeat(np.arange(len(sizes)), sizes)
+    rng = np.random.default_rng(sum(sizes))
+    inp = custom_inputs(rng.integers(150, 260, len(sizes)), rng.integers(1, 60, len(gos)), gos, 28, 4, seed=9)
     check_attn(inp, B.MARL_OUT_F32)
+    check_attn(inp, B.MARL_OUT_F32, prefix_chunk_tokens=64)
 
 
 def test_many_groups_use_the_general_plan_kernel():

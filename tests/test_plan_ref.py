@@ -23,7 +23,7 @@ def test_every_token_is_covered_exactly_once():
         items = [(a, b, r) for (i, a, b, r) in p.prefix_items if i == g]
         cover = np.zeros((max(rows, 1), max(int(pl[g]), 1)), int)
         for a, b, r in items:
-            cover[r:min(rows, r + plan_ref.ROWS_PER_QBLOCK), a:b] += 1
+            cover[r:min(rows, r + plan_ref.rows_per_qblock(NG * G, NG, Hq, Hkv)), a:b] += 1
         if rows and pl[g]:
             assert (cover == 1).all()
         else:
