@@ -350,10 +350,9 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
 //   suffix_kernel:       long items, one per workgroup (waves take the 32-token steps in
 //                        turn), taken from the queue only when the workgroup is free
 //                        (reserving an item early would undo the longest-first balancing).
-//   short_suffix_items:  short items, one per wave, four queue entries per round, with no
-//                        LDS traffic or barrier inside an item, so a batch of tiny sequences
-//                        does not pay a workgroup's fixed costs per sequence; the next
-//                        round's indices and records are fetched while the current one runs.
+//   short_suffix_items:  short items, one per wave, split round-robin over all waves of the
+//                        grid with no LDS traffic, barrier or atomic, so a batch of tiny
+//                        sequences does not pay a workgroup's fixed costs per sequence.
 //                        It runs as the first phase of the PREFIX kernel's workgroups: as a
 //                        phase of the suffix kernel it slowed the long items' hot loop down
 //                        by a few percent (shared register allocation), as a kernel of its
@@ -374,11 +373,16 @@ void suffix_kernel(AttnArgs a) {
   __shared__ int next_item;
   const int n_work = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
   int bad_page = 0;
-  for (;;) {
-    if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_SUFFIX_CURSOR], 1);
-    __syncthreads();
-    const int qi = next_item;
-    __syncthreads();
+  // the first item of a workgroup is its block index (no trip to the shared counter, on which
+  // a whole grid starting at once would queue up); later ones come from the counter
+  for (bool first = true;; first = false) {
+    int qi = blockIdx.x;
+    if (!first) {
+      if (threadIdx.x == 0) next_item = gridDim.x + atomicAdd(&a.counters[MARL_CTR_SUFFIX_CURSOR], 1);
+      __syncthreads();
+      qi = next_item;
+      __syncthreads();
+    }
     if (qi >= n_work) break;
     const int4 it = a.suffix_items[qi / a.Hkv];
     const int kvh = qi % a.Hkv;
@@ -391,52 +395,30 @@ void suffix_kernel(AttnArgs a) {
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }
 
-template <int NW>
-__device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int4 (&s_rec)[2][NW], int (&s_idx)[2], int& bad_page) {
-  const int tid = threadIdx.x;
+// Short suffix items: wave w of the grid takes the entries n_long + w, n_long + w + W, ...
+// (W = waves in the grid) with no LDS, no barrier and no atomic: the entries are sorted by
+// size, so a round-robin split is balanced, and a shared queue counter would serialise
+// thousands of waves on one address.  The next record is fetched while the current item runs.
+__device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int& bad_page) {
   const int n_long = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
   const int n_work = a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] * a.Hkv;
-  if (n_long >= n_work) return;
-  const int i = tid & 15;
-  const int wave = tid >> 6;
-  if (tid < NW) {
-    int i0 = 0, i1 = 0;
-    if (tid == 0) {
-      i0 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], NW);
-      i1 = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], NW);
-      s_idx[0] = i0;
-      s_idx[1] = i1;
-    }
-    i0 = __shfl(i0, 0) + tid;
-    if (i0 < n_work) s_rec[0][tid] = a.suffix_items[i0 / a.Hkv];
-  }
-  __syncthreads();
-  for (int b = 0;; b ^= 1) {
-    const int base = s_idx[b];
-    if (base >= n_work) break;
-    const int qi = base + wave;
-    const int4 it = s_rec[b][wave];
-    __syncthreads();   // everybody has read this round's slots before they are refilled
-    int inew = 0;
-    int4 nrec = make_int4(0, 0, 0, 0);
-    if (tid < NW) {
-      const int inext = s_idx[b ^ 1] + tid;
-      if (inext < n_work) nrec = a.suffix_items[inext / a.Hkv];
-      if (tid == 0) inew = n_long + atomicAdd(&a.counters[MARL_CTR_SHORT_CURSOR], NW);
-    }
-    if (qi < n_work) {   // wave-uniform
-      const int kvh = qi % a.Hkv;
-      const int s = it.x;
-      const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
-      ItemLds<1>* no_lds = nullptr;   // the one-wave path never touches it
-      process_item<1, 1>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
-                         a.NCp + it.y / a.Cs, *no_lds, bad_page);
-    }
-    if (tid < NW) {
-      s_rec[b ^ 1][tid] = nrec;
-      if (tid == 0) s_idx[b] = inew;
-    }
-    __syncthreads();
+  const int waves_per_block = blockDim.x >> 6;
+  const int stride = gridDim.x * waves_per_block;
+  int cur = n_long + blockIdx.x * waves_per_block + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (cur >= n_work) return;
+  const int i = threadIdx.x & 15;
+  int4 rec = a.suffix_items[cur / a.Hkv];
+  while (cur < n_work) {
+    const int nxt = cur + stride;
+    const int4 nrec = nxt < n_work ? a.suffix_items[nxt / a.Hkv] : make_int4(0, 0, 0, 0);
+    const int kvh = cur % a.Hkv;
+    const int s = rec.x;
+    const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
+    ItemLds<1>* no_lds = nullptr;   // the one-wave path never touches it
+    process_item<1, 1>(a, a.suffix_table + (size_t)s * a.max_sp, rec.y, rec.z, kvh, row_index,
+                       a.NCp + rec.y / a.Cs, *no_lds, bad_page);
+    cur = nxt;
+    rec = nrec;
   }
 }
 
@@ -690,20 +672,21 @@ template <int NW>
 __device__ __forceinline__ void prefix_kernel_body(const AttnArgs& a) {
   __shared__ PrefixLds lds;
   __shared__ int next_item;
-  __shared__ int s_idx[2];          // short suffix items: first queue index of this / the next round
-  __shared__ int4 s_rec[2][NW];     // and their item records
   const int n_work = a.counters[MARL_CTR_NUM_PREFIX_ITEMS] * a.Hkv;
   int bad_page = 0;
   // The short suffix items go first: each round is a chain of dependent memory accesses with
   // little data, which is cheap while every workgroup has other work to overlap it with and
   // expensive at the tail of a kernel, where only a few workgroups are left.
-  short_suffix_items<NW>(a, s_rec, s_idx, bad_page);
+  short_suffix_items(a, bad_page);
   __syncthreads();
-  for (;;) {
-    if (threadIdx.x == 0) next_item = atomicAdd(&a.counters[MARL_CTR_PREFIX_CURSOR], 1);
-    __syncthreads();
-    const int qi = next_item;
-    __syncthreads();
+  for (bool first = true;; first = false) {   // first item = block index, as in the suffix kernel
+    int qi = blockIdx.x;
+    if (!first) {
+      if (threadIdx.x == 0) next_item = gridDim.x + atomicAdd(&a.counters[MARL_CTR_PREFIX_CURSOR], 1);
+      __syncthreads();
+      qi = next_item;
+      __syncthreads();
+    }
     if (qi >= n_work) break;
     const int4 it = a.prefix_items[qi / a.Hkv];
     const int kvh = qi % a.Hkv;
