@@ -104,3 +104,28 @@ def test_profile_argument_errors():
     lib = B.load_library()
     assert lib.marl_profile_begin(0) == -1
     assert lib.marl_profile_end(None, None, None) == -1
+
+
+def test_kv_cache_argument_errors_without_gpu():
+    lib = B.load_library()
+    shape = good_shape()
+    buf = ctypes.create_string_buffer(1024)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    ap = lambda k_new, lens, sh=shape: lib.marl_kv_append(ctypes.byref(sh), k_new, p, p, p, p, lens, None, None)
+    assert ap(None, p) == -1 and ap(p, None) == -1
+    assert ap(p, p, good_shape(max_suffix_pages=0)) == -1          # no room for any token
+    assert ap(p, p, good_shape(head_dim=64)) == -2
+    assert ap(p, p, good_shape(num_seqs=0)) == 0                   # nothing to do
+    cp = lambda src, n: lib.marl_kv_copy_pages(ctypes.byref(shape), p, p, src, p, n, None, None)
+    assert cp(p, -1) == -1 and cp(None, 3) == -1 and cp(p, 0) == 0
+
+
+def test_plan_entry_argument_errors_without_gpu():
+    lib = B.load_library()
+    shape = good_shape()
+    need = B.marl_workspace_bytes(shape)
+    buf = ctypes.create_string_buffer(need + 512)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    assert lib.marl_attn_plan(ctypes.byref(shape), p, need, None, p, p, None) == -1
+    assert lib.marl_attn_plan(ctypes.byref(shape), p, need - 256, p, p, p, None) == -3
+    assert lib.marl_attn_read_flags(None, None, None) == -1
