@@ -178,6 +178,21 @@ def main():
             tot += ev0.elapsed_time(ev1)
     res["kv_append"] = {"us_per_call": tot / n_app * 1e3, "tokens": w.num_seqs,
                         "bytes_written": w.num_seqs * w.Hkv * 128 * 2 * 2}
+    # sampling fused with the log-probability (one more row beyond the timed step)
+    uniforms = torch.rand(w.num_seqs, device=dev, generator=torch.Generator(device=dev).manual_seed(3))
+    s_ws = B.alloc_workspace(B.marl_sample_workspace_bytes(w.num_seqs, vocab), dev)
+    s_tok = torch.empty(w.num_seqs, dtype=torch.int32, device=dev)
+    s_lp = torch.empty(w.num_seqs, dtype=torch.float32, device=dev)
+    tot = 0.0
+    for it in range(12):
+        ev0.record()
+        B.marl_sample_tokens(lp.logits, uniforms, lp.temperature, s_tok, s_lp, s_ws)
+        ev1.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            tot += ev0.elapsed_time(ev1)
+    res["sample_tokens"] = {"us_per_call": tot / 10 * 1e3, "rows": w.num_seqs,
+                            "GBps": w.num_seqs * vocab * 2 / (tot / 10 * 1e-3) / 1e9}
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
     print(json.dumps(res))

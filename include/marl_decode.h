@@ -199,6 +199,23 @@ int marl_token_logprobs(const void* logits, const int32_t* tokens, float tempera
                         void* stream);
 
 /*
+ * Draws one token per row from softmax(logits / T) by inverse CDF and returns its
+ * log-probability, with one streaming pass over the logits (plus 8 KB per row):
+ *   p_v = softmax(logits[r, :] / T)_v,  token[r] = min { t : sum_{v <= t} p_v > uniforms[r] },
+ *   logprob[r] = log p_{token[r]}.
+ * uniforms: device float32 [rows] in [0, 1), supplied by the caller (the library draws no
+ * random numbers).  If rounding leaves no such t, the last token with non-zero probability is
+ * returned.  The sums run in float32, so for a uniform within ~1e-6 of a CDF step the
+ * neighbouring token may be returned.  A row without any finite logit gives token -1 and NaN.
+ * out_tokens int32 [rows], out_logprobs float32 [rows]; workspace of
+ * marl_sample_workspace_bytes() bytes, 8-byte aligned.  Other arguments as marl_token_logprobs.
+ */
+int marl_sample_workspace_bytes(int32_t rows, int32_t vocab, size_t* bytes);
+int marl_sample_tokens(const void* logits, const float* uniforms, float temperature,
+                       int32_t* out_tokens, float* out_logprobs, int32_t rows, int32_t vocab,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Per-kernel timing of marl_decode_attn / marl_token_logprobs calls (for benchmarks).
  * After marl_profile_begin(max_calls) every call records HIP events around each of its
  * kernels on the call's stream (no synchronisation).  marl_profile_end() synchronises the

@@ -205,3 +205,36 @@ def kv_copy_pages(k_pages, v_pages, src, dst):
         k_pages[b] = k_pages[a]
         v_pages[b] = v_pages[a]
     return k_pages, v_pages, flags
+
+
+# ------------------------------------------------------------------------------------------
+# Inverse-CDF sampling from softmax(logits / T) with a caller-supplied uniform number, and the
+# drawn token's log-probability (textbook definitions; the paper trains with GRPO, Section 8.1,
+# which consumes the log-probabilities of sampled tokens, and prints no formula).
+# ------------------------------------------------------------------------------------------
+def softmax_cdf(logit_bits_row: np.ndarray, temperature: float):
+    """Probabilities and their running sum for one row of bf16 bit patterns, in float64."""
+    y = bf16_bits_to_f64(logit_bits_row) / float(temperature)
+    m = y.max()
+    w = np.exp(y - m) if np.isfinite(m) else np.zeros_like(y)
+    Z = w.sum()
+    p = w / Z if Z > 0 else w
+    return p, np.cumsum(p)
+
+
+def sample_tokens(logit_bits: np.ndarray, uniforms, temperature: float):
+    """token[r] = first t whose cumulative probability exceeds uniforms[r] (the last token
+    with non-zero probability if none does), and log p of that token.  Rows without a finite
+    logit give (-1, nan)."""
+    rows = logit_bits.shape[0]
+    tokens = np.full(rows, -1, dtype=np.int64)
+    logprobs = np.full(rows, np.nan)
+    for r in range(rows):
+        p, cdf = softmax_cdf(logit_bits[r], temperature)
+        if not (p > 0).any():
+            continue
+        hit = np.nonzero(cdf > float(uniforms[r]))[0]
+        t = int(hit[0]) if hit.size else int(np.nonzero(p > 0)[0][-1])
+        tokens[r] = t
+        logprobs[r] = np.log(p[t])
+    return tokens, logprobs

@@ -75,6 +75,9 @@ def load_library(build_if_missing: bool = True):
     lib.marl_kv_append.argtypes = [PS, VP, VP, VP, VP, VP, VP, VP, VP]
     lib.marl_kv_copy_pages.argtypes = [PS, VP, VP, VP, VP, I32, VP, VP]
     lib.marl_kv_append.restype = lib.marl_kv_copy_pages.restype = ctypes.c_int
+    lib.marl_sample_workspace_bytes.argtypes = [I32, I32, ctypes.POINTER(SZ)]
+    lib.marl_sample_tokens.argtypes = [VP, VP, ctypes.c_float, VP, VP, I32, I32, VP, SZ, VP]
+    lib.marl_sample_workspace_bytes.restype = lib.marl_sample_tokens.restype = ctypes.c_int
     lib.marl_profile_begin.argtypes = [I32]
     lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
     for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_attn_plan",
@@ -194,6 +197,23 @@ def marl_kv_copy_pages(shape: AttnShape, k_pages, v_pages, src, dst, flags: Opti
     rc = load_library().marl_kv_copy_pages(ctypes.byref(shape), _ptr(k_pages), _ptr(v_pages), _ptr(src), _ptr(dst),
                                            int(src.numel()), _ptr(flags), _stream(k_pages.device))
     _check(rc, "marl_kv_copy_pages")
+
+
+def marl_sample_workspace_bytes(rows: int, vocab: int) -> int:
+    n = SZ(0)
+    _check(load_library().marl_sample_workspace_bytes(rows, vocab, ctypes.byref(n)), "marl_sample_workspace_bytes")
+    return int(n.value)
+
+
+def marl_sample_tokens(logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, out_tokens: torch.Tensor,
+                       out_logprobs: torch.Tensor, workspace: torch.Tensor):
+    _require_cuda(logits, uniforms, out_tokens, out_logprobs, workspace)
+    rows, vocab = logits.shape
+    rc = load_library().marl_sample_tokens(_ptr(logits), _ptr(uniforms), float(temperature), _ptr(out_tokens),
+                                           _ptr(out_logprobs), rows, vocab, _ptr(workspace), workspace.numel(),
+                                           _stream(logits.device))
+    _check(rc, "marl_sample_tokens")
+    return out_tokens, out_logprobs
 
 
 def marl_profile_begin(max_calls: int):

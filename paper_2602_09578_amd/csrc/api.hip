@@ -397,6 +397,45 @@ int marl_token_logprobs(const void* logits, const int32_t* tokens, float tempera
   return MARL_OK;
 }
 
+// ---- sampling -----------------------------------------------------------------------------------
+int marl_sample_workspace_bytes(int32_t rows, int32_t vocab, size_t* bytes) {
+  if (!bytes || rows < 0 || vocab < 1) return MARL_INVALID_ARG;
+  *bytes = (size_t)rows * marl::sample_num_chunks(vocab) * sizeof(float2);
+  return MARL_OK;
+}
+
+int marl_sample_tokens(const void* logits, const float* uniforms, float temperature,
+                       int32_t* out_tokens, float* out_logprobs, int32_t rows, int32_t vocab,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (rows < 0 || vocab < 1) return MARL_INVALID_ARG;
+  if (!isfinite(temperature) || !(temperature > 0.f)) return MARL_INVALID_ARG;
+  if (rows == 0) return MARL_OK;
+  if (!logits || !uniforms || !out_tokens || !out_logprobs || !workspace) return MARL_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(logits) % 2 != 0 || reinterpret_cast<uintptr_t>(workspace) % 8 != 0)
+    return MARL_INVALID_ARG;
+  marl::SampleArgs a;
+  memset(&a, 0, sizeof a);
+  a.num_chunks = marl::sample_num_chunks(vocab);
+  if (workspace_bytes < (size_t)rows * a.num_chunks * sizeof(float2)) return MARL_WORKSPACE_TOO_SMALL;
+  // a workgroup (4 waves) covers 4 * chunks_per_wave chunks of a row; aim for >= 2048 workgroups
+  const long want_groups = rows >= 2048 ? 1 : (2048 + rows - 1) / rows;
+  long cpw = (a.num_chunks + 4 * want_groups - 1) / (4 * want_groups);
+  if (cpw < 1) cpw = 1;
+  a.chunks_per_wave = (int32_t)cpw;
+  a.groups_per_row = (int32_t)((a.num_chunks + 4 * cpw - 1) / (4 * cpw));
+  if ((long)rows * a.groups_per_row >= (1L << 31)) return MARL_UNSUPPORTED;
+  a.logits = static_cast<const uint16_t*>(logits);
+  a.uniforms = uniforms;
+  a.out_tokens = out_tokens;
+  a.out_logprobs = out_logprobs;
+  a.partials = static_cast<float2*>(workspace);
+  a.rows = rows;
+  a.vocab = vocab;
+  a.inv_temp_log2e = 1.44269504088896340736f / temperature;
+  const hipError_t e = marl::launch_sample(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "sampling kernels");
+}
+
 // ---- profiling ----------------------------------------------------------------------------------
 int marl_profile_begin(int32_t max_calls) {
   if (max_calls < 1 || max_calls > (1 << 20)) return MARL_INVALID_ARG;

@@ -90,4 +90,16 @@ struct LogprobArgs {
 hipError_t launch_logprobs(const LogprobArgs& a, hipStream_t st);
 hipError_t launch_logprobs_finish(const LogprobArgs& a, hipStream_t st);
 
+struct SampleArgs {
+  const uint16_t* logits;
+  const float* uniforms;
+  int32_t* out_tokens;
+  float* out_logprobs;
+  float2* partials;      // [rows][num_chunks] (max, sum) of each 4096-logit chunk, base-2 units
+  int32_t rows, vocab, num_chunks, chunks_per_wave, groups_per_row;
+  float inv_temp_log2e;
+};
+int sample_num_chunks(int vocab);
+hipError_t launch_sample(const SampleArgs& a, hipStream_t st);
+
 }  // namespace marl
