@@ -35,19 +35,21 @@ __device__ __forceinline__ void add_one(MaxSum& st, float y) {
   st.m = m;
 }
 
+// c > 0 (it is log2(e) / T), so the max of the scaled values is the scaled max of the raw ones:
+// the scale is applied once to the max and folded into the exponent's fma for the rest.
 __device__ __forceinline__ void add_vec(MaxSum& st, u32x4 v, float c) {
-  float y[8];
+  float x[8];
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    y[2 * d] = __uint_as_float(v[d] << 16) * c;
-    y[2 * d + 1] = __uint_as_float(v[d] & 0xffff0000u) * c;
+    x[2 * d] = __uint_as_float(v[d] << 16);
+    x[2 * d + 1] = __uint_as_float(v[d] & 0xffff0000u);
   }
-  const float m8 = fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])), fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7])));
-  const float m = fmaxf(st.m, m8);
+  const float x8 = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+  const float m = fmaxf(st.m, x8 * c);
   const float ms = (m == -INFINITY) ? 0.f : m;
   float sum = 0.f;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) sum += ex2(y[e] - ms);
+  for (int e = 0; e < 8; ++e) sum += ex2(__builtin_fmaf(x[e], c, -ms));
   st.s = st.s * ex2(st.m - ms) + sum;
   st.m = m;
 }
