@@ -216,6 +216,24 @@ int marl_sample_tokens(const void* logits, const float* uniforms, float temperat
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Group-normalised advantages of GRPO (Shao et al. 2024; the paper trains every agent with
+ * GRPO, Section 8.1).  For each group g (the samples of one prompt) with members
+ * group_seqs[group_start[g] .. group_start[g+1]):
+ *   mean_g = average reward of the members,  std_g = sqrt(average squared deviation),
+ *   out[s] = (rewards[s] - mean_g) / (std_g + eps)   for every member s.
+ * A member whose deviation is exactly 0 gets 0 (so a group of equal rewards gives zeros also
+ * with eps = 0).  Sequences that belong to no group keep whatever out held.
+ * Device arrays: rewards float32 [num_seqs], group_start int32 [num_groups + 1] (non-
+ * decreasing, group_start[0] >= 0), group_seqs int32 (sequence ids in [0, num_seqs), each at
+ * most once), out float32 [num_seqs].  The plan of marl_decode_attn leaves exactly these two
+ * index arrays in its workspace (group_start_off, group_seqs_off of the plan layout).
+ * eps must be finite and >= 0.  Contents of the index arrays are not validated.
+ */
+int marl_grpo_advantages(const float* rewards, const int32_t* group_start,
+                         const int32_t* group_seqs, int32_t num_groups, float eps, float* out,
+                         void* stream);
+
+/*
  * Per-kernel timing of marl_decode_attn / marl_token_logprobs calls (for benchmarks).
  * After marl_profile_begin(max_calls) every call records HIP events around each of its
  * kernels on the call's stream (no synchronisation).  marl_profile_end() synchronises the

@@ -238,3 +238,25 @@ def sample_tokens(logit_bits: np.ndarray, uniforms, temperature: float):
         tokens[r] = t
         logprobs[r] = np.log(p[t])
     return tokens, logprobs
+
+
+# ------------------------------------------------------------------------------------------
+# GRPO's group-normalised advantage (Shao et al. 2024, the algorithm the paper trains with,
+# Section 8.1): reward minus the group mean, over the group's standard deviation (the root of
+# the mean squared deviation) plus eps.
+# ------------------------------------------------------------------------------------------
+def grpo_advantages(rewards, group_of_seq, num_groups: int, eps: float):
+    """rewards [NS], group_of_seq [NS] (ids outside [0, num_groups) belong to no group and
+    give nan) -> float64 [NS]."""
+    r = np.asarray(rewards, dtype=np.float64)
+    g = np.asarray(group_of_seq)
+    out = np.full(r.shape, np.nan)
+    for k in range(num_groups):
+        idx = np.nonzero(g == k)[0]
+        if idx.size == 0:
+            continue
+        dev = r[idx] - r[idx].mean()
+        std = np.sqrt((dev * dev).mean())
+        for i, d in zip(idx, dev):
+            out[i] = 0.0 if d == 0.0 else d / (std + eps)
+    return out

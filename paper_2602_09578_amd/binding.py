@@ -78,6 +78,8 @@ def load_library(build_if_missing: bool = True):
     lib.marl_sample_workspace_bytes.argtypes = [I32, I32, ctypes.POINTER(SZ)]
     lib.marl_sample_tokens.argtypes = [VP, VP, ctypes.c_float, VP, VP, I32, I32, VP, SZ, VP]
     lib.marl_sample_workspace_bytes.restype = lib.marl_sample_tokens.restype = ctypes.c_int
+    lib.marl_grpo_advantages.argtypes = [VP, VP, VP, I32, ctypes.c_float, VP, VP]
+    lib.marl_grpo_advantages.restype = ctypes.c_int
     lib.marl_profile_begin.argtypes = [I32]
     lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
     for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_attn_plan",
@@ -214,6 +216,16 @@ def marl_sample_tokens(logits: torch.Tensor, uniforms: torch.Tensor, temperature
                                            _stream(logits.device))
     _check(rc, "marl_sample_tokens")
     return out_tokens, out_logprobs
+
+
+def marl_grpo_advantages(rewards: torch.Tensor, group_start: torch.Tensor, group_seqs: torch.Tensor, eps: float,
+                         out: torch.Tensor):
+    _require_cuda(rewards, group_start, group_seqs, out)
+    rc = load_library().marl_grpo_advantages(_ptr(rewards), _ptr(group_start), _ptr(group_seqs),
+                                             int(group_start.numel()) - 1, float(eps), _ptr(out),
+                                             _stream(rewards.device))
+    _check(rc, "marl_grpo_advantages")
+    return out
 
 
 def marl_profile_begin(max_calls: int):

@@ -436,6 +436,23 @@ int marl_sample_tokens(const void* logits, const float* uniforms, float temperat
   return e == hipSuccess ? MARL_OK : hip_fail(e, "sampling kernels");
 }
 
+// ---- GRPO advantages ----------------------------------------------------------------------------
+int marl_grpo_advantages(const float* rewards, const int32_t* group_start, const int32_t* group_seqs,
+                         int32_t num_groups, float eps, float* out, void* stream) {
+  if (num_groups < 0 || !isfinite(eps) || eps < 0.f) return MARL_INVALID_ARG;
+  if (num_groups == 0) return MARL_OK;
+  if (!rewards || !group_start || !group_seqs || !out) return MARL_INVALID_ARG;
+  marl::GrpoArgs a;
+  a.rewards = rewards;
+  a.group_start = group_start;
+  a.group_seqs = group_seqs;
+  a.out = out;
+  a.num_groups = num_groups;
+  a.eps = eps;
+  const hipError_t e = marl::launch_grpo_advantages(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "advantage kernel");
+}
+
 // ---- profiling ----------------------------------------------------------------------------------
 int marl_profile_begin(int32_t max_calls) {
   if (max_calls < 1 || max_calls > (1 << 20)) return MARL_INVALID_ARG;

@@ -102,4 +102,14 @@ struct SampleArgs {
 int sample_num_chunks(int vocab);
 hipError_t launch_sample(const SampleArgs& a, hipStream_t st);
 
+struct GrpoArgs {
+  const float* rewards;        // [num_seqs]
+  const int32_t* group_start;  // [num_groups + 1]
+  const int32_t* group_seqs;   // member lists, group after group
+  float* out;                  // [num_seqs]
+  int32_t num_groups;
+  float eps;
+};
+hipError_t launch_grpo_advantages(const GrpoArgs& a, hipStream_t st);
+
 }  // namespace marl

@@ -129,3 +129,13 @@ def test_plan_entry_argument_errors_without_gpu():
     assert lib.marl_attn_plan(ctypes.byref(shape), p, need, None, p, p, None) == -1
     assert lib.marl_attn_plan(ctypes.byref(shape), p, need - 256, p, p, p, None) == -3
     assert lib.marl_attn_read_flags(None, None, None) == -1
+
+
+def test_grpo_argument_errors_without_gpu():
+    lib = B.load_library()
+    buf = ctypes.create_string_buffer(1024)
+    p = ctypes.c_void_p(ctypes.addressof(buf))
+    f = lambda r, ng, eps: lib.marl_grpo_advantages(r, p, p, ng, ctypes.c_float(eps), p, None)
+    assert f(p, -1, 0.0) == -1 and f(p, 2, -1e-3) == -1 and f(p, 2, float("inf")) == -1
+    assert f(None, 2, 0.0) == -1
+    assert f(None, 0, 0.0) == 0                                    # nothing to do
