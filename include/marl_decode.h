@@ -216,6 +216,58 @@ int marl_sample_tokens(const void* logits, const float* uniforms, float temperat
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Prefill (prompt) attention: the step that creates a prompt's KV prefix, which all samples of
+ * that prompt then share (the paper's Parallel Sampling, Section 5.1; the computation itself is
+ * textbook causal attention, the paper gives no formula).  Group g brings
+ * n_g = q_start[g+1] - q_start[g] query tokens, rows q_start[g] .. of q, at positions
+ * q_pos0[g] .. q_pos0[g] + n_g - 1 of its prompt (q_pos0 > 0: the earlier positions were
+ * prefilled before).  The keys and values of positions 0 .. q_pos0[g] + n_g - 1 must already be
+ * in the pages listed in prefix_block_table[g] (marl_kv_write_prompt puts a chunk there).
+ *   out[t, h, :] = softmax_j( scale * <q[t, h, :], K[j, h / R, :]> ) V[j, h / R, :],
+ *   j = 0 .. position of t (inclusive),  R = num_q_heads / num_kv_heads.
+ * Device arrays: q bf16 [num_tokens, Hq, 128]; k_pages / v_pages / prefix_block_table as in
+ * marl_decode_attn; q_start int32 [num_groups + 1] (non-decreasing, within [0, num_tokens]);
+ * q_pos0 int32 [num_groups]; out bf16 or float32 [num_tokens, Hq, 128].  Rows of q that no
+ * group covers keep whatever out held.  A group whose tokens do not fit its table row is cut
+ * short (MARL_FLAG_LEN_CLAMPED), an inconsistent q_start / q_pos0 entry drops the group
+ * (MARL_FLAG_BAD_GROUP), a page id out of range reads page 0 (MARL_FLAG_BAD_PAGE); read the
+ * flags with marl_attn_read_flags on this call's workspace.
+ * workspace: marl_prefill_workspace_bytes() bytes, 256-byte aligned, used from the start of the
+ * call's work until its end on the stream.
+ */
+typedef struct {
+  int32_t num_tokens;        /* NT: query tokens of all groups together */
+  int32_t num_groups;        /* NG */
+  int32_t num_q_heads;       /* Hq */
+  int32_t num_kv_heads;      /* Hkv, divides Hq, Hq / Hkv <= 16 */
+  int32_t head_dim;          /* 128 */
+  int32_t page_size;         /* 16 */
+  int32_t num_pages;         /* extent of k_pages / v_pages */
+  int32_t max_prefix_pages;  /* row stride of prefix_block_table */
+  int32_t out_dtype;         /* MARL_OUT_BF16 or MARL_OUT_F32 */
+  int32_t reserved;          /* 0 */
+} marl_prefill_shape;
+
+int marl_prefill_workspace_bytes(const marl_prefill_shape* shape, size_t* bytes);
+int marl_prefill_attn(const marl_prefill_shape* shape, void* workspace, size_t workspace_bytes,
+                      const void* q, const void* k_pages, const void* v_pages,
+                      const int32_t* prefix_block_table, const int32_t* q_start,
+                      const int32_t* q_pos0, float scale, void* out, void* stream);
+
+/*
+ * Scatter of prompt keys / values into the pages: token q_start[g] + tau of k_new / v_new
+ * (bf16 [num_tokens, Hkv, 128]) goes to position q_pos0[g] + tau of group g, i.e. page
+ * prefix_block_table[g][pos / 16], slot pos % 16 (K [page][kv_head][slot][128],
+ * V [page][kv_head][128][slot]).  Tokens that do not fit, belong to no group or point to a
+ * page out of range are skipped and flagged in *flags (device int32, may be NULL; OR-ed, the
+ * caller zeroes it).  Bit-exact data movement.
+ */
+int marl_kv_write_prompt(const marl_prefill_shape* shape, const void* k_new, const void* v_new,
+                         void* k_pages, void* v_pages, const int32_t* prefix_block_table,
+                         const int32_t* q_start, const int32_t* q_pos0, int32_t* flags,
+                         void* stream);
+
+/*
  * Group-normalised advantages of GRPO (Shao et al. 2024; the paper trains every agent with
  * GRPO, Section 8.1).  For each group g (the samples of one prompt) with members
  * group_seqs[group_start[g] .. group_start[g+1]):

@@ -260,3 +260,60 @@ def grpo_advantages(rewards, group_of_seq, num_groups: int, eps: float):
         for i, d in zip(idx, dev):
             out[i] = 0.0 if d == 0.0 else d / (std + eps)
     return out
+
+
+# ------------------------------------------------------------------------------------------
+# Prompt (prefill) attention: textbook causal attention over the logical positions of a
+# group's pages, and the scatter of a prompt chunk into the pages (the step that creates the
+# prefix all samples of a prompt share, Section 5.1 of the paper, which prints no formula).
+# ------------------------------------------------------------------------------------------
+def gather_group_kv(k_pages, v_pages, table_row, length: int):
+    """Logical K and V of one block-table row as float64 [length, Hkv, 128]."""
+    Hkv = k_pages.shape[1]
+    K = np.zeros((length, Hkv, 128))
+    V = np.zeros((length, Hkv, 128))
+    for t in range(length):
+        page, slot = int(table_row[t // 16]), t % 16
+        K[t] = bf16_bits_to_f64(k_pages[page, :, slot, :])
+        V[t] = bf16_bits_to_f64(v_pages[page, :, :, slot])
+    return K, V
+
+
+def prefill_attn(q, k_pages, v_pages, prefix_table, q_start, q_pos0, scale: float, Hq: int, Hkv: int):
+    """q uint16 [NT, Hq, 128] (bf16 bits); returns float64 [NT, Hq, 128].  Query token tau of group g
+    sits at position q_pos0[g] + tau and attends to positions 0 .. its own (inclusive).  Rows no
+    group covers are nan."""
+    q, k_pages, v_pages = _u16(q), _u16(k_pages), _u16(v_pages)
+    NT = q.shape[0]
+    R = Hq // Hkv
+    out = np.full((NT, Hq, 128), np.nan)
+    qs = np.asarray(q_start, dtype=np.int64)
+    for g in range(len(q_pos0)):
+        b, e, p0 = int(qs[g]), int(qs[g + 1]), int(q_pos0[g])
+        n = e - b
+        if n <= 0:
+            continue
+        L = p0 + n
+        K, V = gather_group_kv(k_pages, v_pages, np.asarray(prefix_table)[g], L)
+        Q = bf16_bits_to_f64(q[b:e])                          # [n, Hq, 128]
+        visible = np.arange(L)[None, :] <= (p0 + np.arange(n))[:, None]
+        for h in range(Hq):
+            x = float(scale) * (Q[:, h, :] @ K[:, h // R, :].T)     # [n, L]
+            x = np.where(visible, x, -np.inf)
+            w = np.exp(x - x.max(axis=1, keepdims=True))
+            out[b:e, h, :] = (w / w.sum(axis=1, keepdims=True)) @ V[:, h // R, :]
+    return out
+
+
+def kv_write_prompt(k_pages, v_pages, prefix_table, q_start, q_pos0, k_new, v_new):
+    """Token q_start[g] + tau goes to position q_pos0[g] + tau of group g.  Returns new arrays."""
+    k_pages, v_pages = k_pages.copy(), v_pages.copy()
+    table = np.asarray(prefix_table)
+    for g in range(len(q_pos0)):
+        for tau in range(int(q_start[g + 1]) - int(q_start[g])):
+            pos = int(q_pos0[g]) + tau
+            page, slot = int(table[g, pos // 16]), pos % 16
+            tok = int(q_start[g]) + tau
+            k_pages[page, :, slot, :] = k_new[tok]
+            v_pages[page, :, :, slot] = v_new[tok]
+    return k_pages, v_pages

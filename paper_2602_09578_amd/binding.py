@@ -40,6 +40,12 @@ class PlanLayout(ctypes.Structure):
             "suffix_items_off", "prefix_items_off", "partial_ml_off", "partial_o_off", "total_bytes")]
 
 
+class PrefillShape(ctypes.Structure):
+    _fields_ = [(n, I32) for n in (
+        "num_tokens", "num_groups", "num_q_heads", "num_kv_heads", "head_dim", "page_size",
+        "num_pages", "max_prefix_pages", "out_dtype", "reserved")]
+
+
 class MarlError(RuntimeError):
     def __init__(self, status: int, where: str, detail: str = ""):
         self.status = status
@@ -79,6 +85,12 @@ def load_library(build_if_missing: bool = True):
     lib.marl_sample_tokens.argtypes = [VP, VP, ctypes.c_float, VP, VP, I32, I32, VP, SZ, VP]
     lib.marl_sample_workspace_bytes.restype = lib.marl_sample_tokens.restype = ctypes.c_int
     lib.marl_grpo_advantages.argtypes = [VP, VP, VP, I32, ctypes.c_float, VP, VP]
+    PP = ctypes.POINTER(PrefillShape)
+    lib.marl_prefill_workspace_bytes.argtypes = [PP, ctypes.POINTER(SZ)]
+    lib.marl_prefill_attn.argtypes = [PP, VP, SZ, VP, VP, VP, VP, VP, VP, ctypes.c_float, VP, VP]
+    lib.marl_kv_write_prompt.argtypes = [PP, VP, VP, VP, VP, VP, VP, VP, VP, VP]
+    lib.marl_prefill_workspace_bytes.restype = lib.marl_prefill_attn.restype = ctypes.c_int
+    lib.marl_kv_write_prompt.restype = ctypes.c_int
     lib.marl_grpo_advantages.restype = ctypes.c_int
     lib.marl_profile_begin.argtypes = [I32]
     lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
@@ -226,6 +238,53 @@ def marl_grpo_advantages(rewards: torch.Tensor, group_start: torch.Tensor, group
                                              _stream(rewards.device))
     _check(rc, "marl_grpo_advantages")
     return out
+
+
+def make_prefill_shape(num_tokens, num_groups, num_q_heads, num_kv_heads, num_pages, max_prefix_pages,
+                       out_dtype=MARL_OUT_BF16, head_dim=128, page_size=16) -> PrefillShape:
+    return PrefillShape(num_tokens, num_groups, num_q_heads, num_kv_heads, head_dim, page_size, num_pages,
+                        max_prefix_pages, out_dtype, 0)
+
+
+def marl_prefill_workspace_bytes(shape: PrefillShape) -> int:
+    n = SZ(0)
+    _check(load_library().marl_prefill_workspace_bytes(ctypes.byref(shape), ctypes.byref(n)),
+           "marl_prefill_workspace_bytes")
+    return int(n.value)
+
+
+def marl_prefill_attn(shape: PrefillShape, workspace, q, k_pages, v_pages, prefix_block_table, q_start, q_pos0,
+                      scale: float, out):
+    _require_cuda(workspace, q, k_pages, v_pages, prefix_block_table, q_start, q_pos0, out)
+    rc = load_library().marl_prefill_attn(ctypes.byref(shape), _ptr(workspace), workspace.numel(), _ptr(q),
+                                          _ptr(k_pages), _ptr(v_pages), _ptr(prefix_block_table), _ptr(q_start),
+                                          _ptr(q_pos0), float(scale), _ptr(out), _stream(q.device))
+    _check(rc, "marl_prefill_attn")
+    return out
+
+
+def marl_kv_write_prompt(shape: PrefillShape, k_new, v_new, k_pages, v_pages, prefix_block_table, q_start, q_pos0,
+                         flags=None):
+    _require_cuda(k_new, v_new, k_pages, v_pages, prefix_block_table, q_start, q_pos0, flags)
+    rc = load_library().marl_kv_write_prompt(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_pages),
+                                             _ptr(v_pages), _ptr(prefix_block_table), _ptr(q_start), _ptr(q_pos0),
+                                             _ptr(flags) if flags is not None else None, _stream(k_new.device))
+    _check(rc, "marl_kv_write_prompt")
+
+
+def prepare_prefill(inp, out_dtype=MARL_OUT_BF16):
+    """(shape, workspace, out) for an inputs.PrefillInputs resident on a GPU."""
+    shape = make_prefill_shape(inp.num_tokens, inp.num_groups, inp.Hq, inp.Hkv, inp.num_pages,
+                               int(inp.prefix_block_table.shape[1]), out_dtype)
+    ws = alloc_workspace(marl_prefill_workspace_bytes(shape), inp.q.device)
+    out = torch.empty((inp.num_tokens, inp.Hq, 128), device=inp.q.device,
+                      dtype=torch.bfloat16 if out_dtype == MARL_OUT_BF16 else torch.float32)
+    return shape, ws, out
+
+
+def run_prefill(inp, shape, ws, out):
+    return marl_prefill_attn(shape, ws, inp.q, inp.k_pages, inp.v_pages, inp.prefix_block_table, inp.q_start,
+                             inp.q_pos0, inp.scale, out)
 
 
 def marl_profile_begin(max_calls: int):

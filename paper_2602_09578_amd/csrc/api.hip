@@ -436,6 +436,114 @@ int marl_sample_tokens(const void* logits, const float* uniforms, float temperat
   return e == hipSuccess ? MARL_OK : hip_fail(e, "sampling kernels");
 }
 
+// ---- prefill ------------------------------------------------------------------------------------
+namespace {
+int check_prefill_shape(const marl_prefill_shape* s) {
+  if (!s) return MARL_INVALID_ARG;
+  if (s->num_tokens < 0 || s->num_groups < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 ||
+      s->num_pages < 1 || s->max_prefix_pages < 0)
+    return MARL_INVALID_ARG;
+  if (s->num_q_heads % s->num_kv_heads != 0) return MARL_INVALID_ARG;
+  if (s->head_dim != marl::kD || s->page_size != marl::kPage) return MARL_UNSUPPORTED;
+  if (s->num_q_heads / s->num_kv_heads > 16) return MARL_UNSUPPORTED;
+  if (s->out_dtype != MARL_OUT_BF16 && s->out_dtype != MARL_OUT_F32) return MARL_UNSUPPORTED;
+  if ((long)s->num_tokens * s->num_q_heads >= (1L << 31)) return MARL_UNSUPPORTED;   // 32-bit row indices
+  if ((long)s->max_prefix_pages * marl::kPage >= (1L << 30)) return MARL_UNSUPPORTED;
+  return MARL_OK;
+}
+constexpr size_t kPrefillHeaderBytes = 256;   // counters
+size_t prefill_ws_bytes(const marl_prefill_shape* s) {
+  return kPrefillHeaderBytes + align_up(((size_t)s->num_groups + 1) * sizeof(int32_t), 256);
+}
+void fill_prefill_args(const marl_prefill_shape* s, marl::PrefillArgs& a) {
+  memset(&a, 0, sizeof a);
+  a.NT = s->num_tokens;
+  a.NG = s->num_groups;
+  a.Hq = s->num_q_heads;
+  a.Hkv = s->num_kv_heads;
+  a.R = a.Hq / a.Hkv;
+  a.num_pages = s->num_pages;
+  a.max_pp = s->max_prefix_pages;
+  a.out_dtype = s->out_dtype;
+}
+}  // namespace
+
+int marl_prefill_workspace_bytes(const marl_prefill_shape* shape, size_t* bytes) {
+  const int rc = check_prefill_shape(shape);
+  if (rc != MARL_OK) return rc;
+  if (!bytes) return MARL_INVALID_ARG;
+  *bytes = prefill_ws_bytes(shape);
+  return MARL_OK;
+}
+
+int marl_prefill_attn(const marl_prefill_shape* shape, void* workspace, size_t workspace_bytes,
+                      const void* q, const void* k_pages, const void* v_pages,
+                      const int32_t* prefix_block_table, const int32_t* q_start,
+                      const int32_t* q_pos0, float scale, void* out, void* stream) {
+  const int rc = check_prefill_shape(shape);
+  if (rc != MARL_OK) return rc;
+  if (!isfinite(scale)) return MARL_INVALID_ARG;
+  if (shape->num_tokens == 0 || shape->num_groups == 0) return MARL_OK;
+  if (!workspace || !q || !k_pages || !v_pages || !prefix_block_table || !q_start || !q_pos0 || !out)
+    return MARL_INVALID_ARG;
+  if (shape->max_prefix_pages < 1) return MARL_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || reinterpret_cast<uintptr_t>(q) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(k_pages) % 16 != 0 || reinterpret_cast<uintptr_t>(v_pages) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(out) % 16 != 0)
+    return MARL_INVALID_ARG;
+  if (workspace_bytes < prefill_ws_bytes(shape)) return MARL_WORKSPACE_TOO_SMALL;
+  marl::PrefillArgs a;
+  fill_prefill_args(shape, a);
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_pages = static_cast<const uint16_t*>(k_pages);
+  a.v_pages = static_cast<const uint16_t*>(v_pages);
+  a.prefix_table = prefix_block_table;
+  a.q_start = q_start;
+  a.q_pos0 = q_pos0;
+  a.out = out;
+  a.counters = static_cast<int32_t*>(workspace);
+  a.block_start = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + kPrefillHeaderBytes);
+  a.scale = scale;
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return hip_fail(e, "device query");
+  // no more workgroups than the shape can have row blocks
+  const long max_items = ((long)a.NT * a.R / marl::prefill_rows_per_block() + a.NG) * a.Hkv;
+  long grid = (long)cus * marl::prefill_blocks_per_cu();
+  if (grid > max_items) grid = max_items;
+  if (grid < 1) grid = 1;
+  e = marl::launch_prefill(a, (int)grid, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "prefill kernels");
+}
+
+int marl_kv_write_prompt(const marl_prefill_shape* shape, const void* k_new, const void* v_new,
+                         void* k_pages, void* v_pages, const int32_t* prefix_block_table,
+                         const int32_t* q_start, const int32_t* q_pos0, int32_t* flags,
+                         void* stream) {
+  const int rc = check_prefill_shape(shape);
+  if (rc != MARL_OK) return rc;
+  if (shape->num_tokens == 0 || shape->num_groups == 0) return MARL_OK;
+  if (!k_new || !v_new || !k_pages || !v_pages || !prefix_block_table || !q_start || !q_pos0)
+    return MARL_INVALID_ARG;
+  if (shape->max_prefix_pages < 1) return MARL_INVALID_ARG;
+  if ((long)shape->num_tokens * shape->num_kv_heads >= (1L << 31)) return MARL_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(k_new) % 16 != 0 || reinterpret_cast<uintptr_t>(k_pages) % 16 != 0)
+    return MARL_INVALID_ARG;
+  marl::PrefillArgs a;
+  fill_prefill_args(shape, a);
+  a.k_new = static_cast<const uint16_t*>(k_new);
+  a.v_new = static_cast<const uint16_t*>(v_new);
+  a.k_pages_w = static_cast<uint16_t*>(k_pages);
+  a.v_pages_w = static_cast<uint16_t*>(v_pages);
+  a.prefix_table = prefix_block_table;
+  a.q_start = q_start;
+  a.q_pos0 = q_pos0;
+  a.flags = flags;
+  const hipError_t e = marl::launch_kv_write_prompt(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "prompt scatter kernel");
+}
+
 // ---- GRPO advantages ----------------------------------------------------------------------------
 int marl_grpo_advantages(const float* rewards, const int32_t* group_start, const int32_t* group_seqs,
                          int32_t num_groups, float eps, float* out, void* stream) {

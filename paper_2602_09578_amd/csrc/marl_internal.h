@@ -102,6 +102,30 @@ struct SampleArgs {
 int sample_num_chunks(int vocab);
 hipError_t launch_sample(const SampleArgs& a, hipStream_t st);
 
+struct PrefillArgs {
+  const uint16_t* q;            // [NT][Hq][128]
+  const uint16_t* k_pages;
+  const uint16_t* v_pages;
+  const int32_t* prefix_table;  // [NG][max_pp]
+  const int32_t* q_start;       // [NG + 1]
+  const int32_t* q_pos0;        // [NG]
+  void* out;                    // [NT][Hq][128]
+  int32_t* counters;            // workspace header
+  int32_t* block_start;         // [NG + 1] running number of row blocks
+  // the prompt scatter only:
+  const uint16_t* k_new;        // [NT][Hkv][128]
+  const uint16_t* v_new;
+  uint16_t* k_pages_w;
+  uint16_t* v_pages_w;
+  int32_t* flags;
+  int32_t NT, NG, Hq, Hkv, R, num_pages, max_pp, out_dtype;
+  float scale;
+};
+int prefill_rows_per_block();
+int prefill_blocks_per_cu();
+hipError_t launch_prefill(const PrefillArgs& a, int grid, hipStream_t st);
+hipError_t launch_kv_write_prompt(const PrefillArgs& a, hipStream_t st);
+
 struct GrpoArgs {
   const float* rewards;        // [num_seqs]
   const int32_t* group_start;  // [num_groups + 1]

@@ -1,0 +1,422 @@
+// Prefill (prompt) attention over the paged KV cache, and the scatter that puts a prompt's
+// keys and values into its pages.  This is the step that creates, once per prompt, the prefix
+// every sample of that prompt then shares (Parallel Sampling, Section 5.1 of the paper); the
+// paper leaves the computation to its inference backend, so the operation is the textbook
+// causal attention stated in marl_decode.h:
+//   query token at position t of group g attends to positions 0..t of the group's pages.
+// A group may bring only a chunk of its prompt (positions pos0 .. pos0+n-1): the earlier
+// positions are then context that is already in the cache (chunked prefill).
+//
+// Structure.  Query rows of a (group, KV head) are flattened as rho = token * R + head-in-group
+// and cut into blocks of kQB rows; one work item = (group, row block, KV head).  The item
+// streams keys/values 0 .. (last position of the block) through a triple-buffered LDS tile,
+// 32 tokens (two pages) per step, exactly as the decode prefix kernel does; the waves split the
+// block's 16-row tiles.  Causality costs little: a block spans kQB / R consecutive tokens, so
+// only its last one or two steps need the per-row mask, and a tile skips steps that lie
+// entirely beyond its rows.  A block sees all of its keys, so the output is normalised and
+// written directly (no partials, no merge).
+//
+// Work distribution: a one-workgroup plan kernel turns q_start into the running number of
+// row blocks per group; workgroups then draw (block, KV head) indices from a counter and find
+// the group by bisection.  Inside a group the blocks are taken last-first (most keys first).
+#include "marl_internal.h"
+#include "wave_ops.h"
+
+namespace marl {
+namespace {
+
+#ifndef MARL_PREFILL_MT
+#define MARL_PREFILL_MT 2
+#endif
+#ifndef MARL_PREFILL_NW
+#define MARL_PREFILL_NW 4
+#endif
+#ifndef MARL_PREFILL_WAVES_PER_EU
+#define MARL_PREFILL_WAVES_PER_EU 2
+#endif
+constexpr int kMT = MARL_PREFILL_MT;          // 16-row tiles per wave
+constexpr int kNW = MARL_PREFILL_NW;          // waves per workgroup
+constexpr int kQB = 16 * kMT * kNW;           // query rows per work item
+constexpr int kPfThreads = 64 * kNW;
+constexpr int kPfStepBytes = 2 * kBlockTok * kD * 2;   // K + V of one 32-token step
+constexpr int kPlanThreadsPf = 1024;
+
+struct PrefillLds {
+  __attribute__((aligned(16))) char buf[3][kPfStepBytes];
+};
+
+// counters at the head of the workspace (same slots as the decode plan uses, so that
+// marl_attn_read_flags reads this workspace too); block_start[NG + 1] follows the header
+constexpr int kPfCursor = MARL_CTR_PREFIX_CURSOR, kPfFlags = MARL_CTR_FLAGS;
+
+// n_g usable query tokens of group g (clamped to the q array and to the table row)
+__device__ __forceinline__ int group_tokens(const PrefillArgs& a, int g, int& flag) {
+  const int b = a.q_start[g], e = a.q_start[g + 1], p0 = a.q_pos0[g];
+  int n = e - b;
+  if (b < 0 || e > a.NT || n < 0 || p0 < 0) { flag |= MARL_FLAG_BAD_GROUP; return 0; }
+  const long room = (long)a.max_pp * kPage - p0;
+  if (n > room) { flag |= MARL_FLAG_LEN_CLAMPED; n = room > 0 ? (int)room : 0; }
+  return n;
+}
+
+__global__ __launch_bounds__(kPlanThreadsPf) void prefill_plan_kernel(PrefillArgs a) {
+  __shared__ int part[kPlanThreadsPf];
+  __shared__ int carry, flags_all;
+  const int tid = threadIdx.x;
+  int flag = 0;
+  if (tid == 0) carry = flags_all = 0;
+  __syncthreads();
+  for (int g0 = 0; g0 < a.NG; g0 += kPlanThreadsPf) {
+    const int g = g0 + tid;
+    int nb = 0;
+    if (g < a.NG) nb = (int)(((long)group_tokens(a, g, flag) * a.R + kQB - 1) / kQB);
+    part[tid] = nb;
+    __syncthreads();
+    for (int d = 1; d < kPlanThreadsPf; d <<= 1) {   // inclusive scan
+      const int v = tid >= d ? part[tid - d] : 0;
+      __syncthreads();
+      part[tid] += v;
+      __syncthreads();
+    }
+    if (g < a.NG) a.block_start[g] = carry + part[tid] - nb;
+    __syncthreads();
+    if (tid == kPlanThreadsPf - 1) carry += part[tid];
+    __syncthreads();
+  }
+  if (flag) atomicOr(&flags_all, flag);
+  __syncthreads();
+  if (tid == 0) {
+    a.block_start[a.NG] = carry;
+    a.counters[kPfCursor] = 0;
+    a.counters[kPfFlags] = flags_all;   // the attention kernel may add MARL_FLAG_BAD_PAGE
+  }
+}
+
+__device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, const int row_begin,
+                                             const int kvh, PrefillLds& lds, int& bad_page) {
+  constexpr int kLoads = 1024 / (kNW * 64);     // 16-byte loads per thread and step (16 KB per step)
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i = lane & 15, j = lane >> 4;
+  int unused = 0;
+  const int ntok = group_tokens(a, g, unused);
+  const int nrows = ntok * a.R;
+  const int qrow0 = a.q_start[g];
+  const int pos0 = a.q_pos0[g];
+  const int32_t* table_row = a.prefix_table + (size_t)g * a.max_pp;
+  const float sc = fmaxf(fabsf(a.scale) * 1.44269504088896340736f, 1e-30f);
+  const uint32_t sign_flip = a.scale < 0.f ? 0x80008000u : 0u;
+  const int rows_here = min(kQB, nrows - row_begin);
+  // keys this block needs: 0 .. position of its last row
+  const int tok_end = pos0 + (row_begin + rows_here - 1) / a.R + 1;
+
+  // this wave's tiles: wave, wave + kNW, ...; tile_lo / tile_hi: fewest / most keys any of its rows sees
+  int row_index[kMT], limit[kMT], tile_lo[kMT], tile_hi[kMT];
+  u32x4 qreg[kMT][4];
+#pragma unroll
+  for (int qt = 0; qt < kMT; ++qt) {
+    const int r0 = (qt * kNW + wave) * 16;            // first row of the tile within the block
+    const int rho = row_begin + r0 + i;
+    tile_lo[qt] = tile_hi[qt] = 0;                    // tile without rows: never computed
+    if (r0 < rows_here) {
+      tile_lo[qt] = pos0 + (row_begin + r0) / a.R + 1;
+      tile_hi[qt] = pos0 + (row_begin + min(r0 + 15, rows_here - 1)) / a.R + 1;
+    }
+    int idx = -1;
+    limit[qt] = 1;
+    if (r0 + i < rows_here) {
+      idx = (qrow0 + rho / a.R) * a.Hq + kvh * a.R + rho % a.R;
+      limit[qt] = pos0 + rho / a.R + 1;
+    }
+    row_index[qt] = idx;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (idx >= 0) {
+        v = *reinterpret_cast<const u32x4*>(a.q + (size_t)idx * kD + (4 * kk + j) * 8);
+        v ^= sign_flip;
+      }
+      qreg[qt][kk] = v;
+    }
+  }
+  f32x4 acc[kMT][8];
+  float m_run[kMT], l_run[kMT];
+#pragma unroll
+  for (int qt = 0; qt < kMT; ++qt) {
+    m_run[qt] = -INFINITY;
+    l_run[qt] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int nsteps = (tok_end + kBlockTok - 1) / kBlockTok;
+  const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
+  const char* dummy = reinterpret_cast<const char*>(a.q);   // any valid 16 bytes
+
+  auto load_ids = [&](int n, int& p0, int& p1) {
+    p0 = -1;
+    p1 = -1;
+    if (n < nsteps) {
+      const int t = n * kBlockTok;
+      p0 = ld_uniform(table_row + (t >> 4));
+      p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
+      if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
+      if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
+    }
+  };
+  // A step is 1024 16-byte vectors: K of page 0, K of page 1, V of page 0, V of page 1 (256
+  // each, contiguous in memory); thread tid fetches vectors tid + k * threads.  K lands in LDS
+  // as 32 token rows of 256 B with the 16-byte chunk index XOR-ed with a key of the row, V as
+  // [page][channel][2 halves of 8 slots] with the unit index XOR-ed with (unit >> 3) & 1, so
+  // that the 8 lanes of one operand read hit 8 different bank groups.
+  const char* src_base[kLoads];
+  int lds_off[kLoads];
+  bool second_page[kLoads];
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    const int v = tid + k * kNW * 64;
+    const int region = v >> 8, w = v & 255;
+    second_page[k] = region & 1;
+    const bool is_v = region >> 1;
+    src_base[k] = reinterpret_cast<const char*>(is_v ? a.v_pages : a.k_pages) + (size_t)kvh * (kPage * kD * 2) + w * 16;
+    const int slot = w >> 4;
+    lds_off[k] = is_v ? 2 * kBlockTok * kD + (region & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
+                      : ((region & 1) * 16 + slot) * 256 + (((w & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)) << 4);
+  }
+  // unconditional loads (a step past the end re-reads 16 valid bytes nobody uses): every wait
+  // in the loop then knows how many younger loads are in flight
+  auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
+    const bool ok = p0 >= 0;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k)
+      st[k] = *reinterpret_cast<const u32x4*>(ok ? src_base[k] + (size_t)(second_page[k] ? p1 : p0) * page_bytes : dummy);
+  };
+  auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) *reinterpret_cast<u32x4*>(buf + lds_off[k]) = st[k];
+  };
+  const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
+  const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
+
+  auto compute = [&](int n, const char* buf) {
+    const int t0 = n * kBlockTok;
+    const bool ragged = t0 + kBlockTok > tok_end;   // workgroup-uniform; only the last step
+    u32x4 pb[kMT];
+    u32x4 kr[2][4];
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ (i & 7)) << 4));
+#pragma unroll
+    for (int qt = 0; qt < kMT; ++qt) {
+      pb[qt] = u32x4{0u, 0u, 0u, 0u};
+      if (t0 < tile_hi[qt]) {   // wave-uniform: some row of the tile sees a token of this step
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          s0 = mfma_16x16x32(kr[0][kk], qreg[qt][kk], s0);
+          s1 = mfma_16x16x32(kr[1][kk], qreg[qt][kk], s1);
+        }
+        if (t0 + kBlockTok > tile_lo[qt]) {   // wave-uniform: the causal edge crosses this step
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (t0 + 8 * j + e >= limit[qt]) s0[e] = -INFINITY;
+            if (t0 + 8 * j + 4 + e >= limit[qt]) s1[e] = -INFINITY;
+          }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                         fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+        mx = rows_allreduce_max(mx);
+        // every row sees token 0, so after step 0 the running max is finite and a fully masked
+        // row of a later step gives alpha = 1, p = 0
+        const float m_new = fmaxf(m_run[qt], mx * sc);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+        float p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], sc, -m_new));
+          p[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], sc, -m_new));
+        }
+        const float psum = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run[qt]) != 0) {   // wave-uniform
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= alpha;
+        }
+        l_run[qt] = l_run[qt] * alpha + psum;
+        m_run[qt] = m_new;
+        pb[qt] = u32x4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+      }
+    }
+    u32x4 vr[8];
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) {
+      const int u = 2 * (16 * ct + i) + (j & 1);
+      vr[ct] = *reinterpret_cast<const u32x4*>(buf + v_rd + ((u ^ ((i >> 2) & 1)) << 4));
+    }
+    if (ragged) {
+      // value slots past the block's last key may hold anything (NaN included): zero them
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const int tok = t0 + 8 * j + 2 * d;
+        const uint32_t mask = (tok < tok_end ? 0x0000ffffu : 0u) | (tok + 1 < tok_end ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) vr[ct][d] &= mask;
+      }
+    }
+#pragma unroll
+    for (int qt = 0; qt < kMT; ++qt)
+      if (t0 < tile_hi[qt]) {
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = mfma_16x16x32(vr[ct], pb[qt], acc[qt][ct]);
+      }
+  };
+
+  // three register stages and three LDS buffers, as in the decode prefix kernel
+  u32x4 st0[kLoads], st1[kLoads], st2[kLoads];
+  int p0, p1;
+  load_ids(0, p0, p1);
+  issue(p0, p1, st0);
+  load_ids(1, p0, p1);
+  issue(p0, p1, st1);
+  load_ids(2, p0, p1);
+  issue(p0, p1, st2);
+  load_ids(3, p0, p1);
+  stage_to_lds(st0, lds.buf[0]);
+  __syncthreads();
+  for (int n = 0; n < nsteps; n += 3) {
+    issue(p0, p1, st0);
+    load_ids(n + 4, p0, p1);
+    compute(n, lds.buf[0]);
+    stage_to_lds(st1, lds.buf[1]);
+    __syncthreads();
+    if (n + 1 < nsteps) {
+      issue(p0, p1, st1);
+      load_ids(n + 5, p0, p1);
+      compute(n + 1, lds.buf[1]);
+      stage_to_lds(st2, lds.buf[2]);
+      __syncthreads();
+    }
+    if (n + 2 < nsteps) {
+      issue(p0, p1, st2);
+      load_ids(n + 6, p0, p1);
+      compute(n + 2, lds.buf[2]);
+      stage_to_lds(st0, lds.buf[0]);
+      __syncthreads();
+    }
+  }
+
+  // lane (i, j) holds channels 16*ct + 4*j .. +3 of q-row i
+#pragma unroll
+  for (int qt = 0; qt < kMT; ++qt) {
+    const float l = rows_allreduce_sum(l_run[qt]);
+    if (row_index[qt] >= 0) {
+      const float inv = 1.0f / l;   // l >= 1: the row's own maximum contributes exp2(0)
+      if (a.out_dtype == MARL_OUT_F32) {
+        float* dst = reinterpret_cast<float*>(a.out) + (size_t)row_index[qt] * kD + 4 * j;
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct] * inv;
+      } else {
+        uint16_t* dst = reinterpret_cast<uint16_t*>(a.out) + (size_t)row_index[qt] * kD + 4 * j;
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) {
+          const f32x4 r = acc[qt][ct] * inv;
+          *reinterpret_cast<uint2*>(dst + 16 * ct) = make_uint2(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]));
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kPfThreads)
+__attribute__((amdgpu_waves_per_eu(MARL_PREFILL_WAVES_PER_EU, MARL_PREFILL_WAVES_PER_EU)))
+void prefill_kernel(PrefillArgs a) {
+  __shared__ PrefillLds lds;
+  __shared__ int next_item;
+  const int n_work = a.block_start[a.NG] * a.Hkv;
+  int bad_page = 0;
+  for (bool first = true;; first = false) {
+    int qi = blockIdx.x;
+    if (!first) {
+      if (threadIdx.x == 0) next_item = gridDim.x + atomicAdd(&a.counters[kPfCursor], 1);
+      __syncthreads();
+      qi = next_item;
+      __syncthreads();
+    }
+    if (qi >= n_work) break;
+    const int b = qi / a.Hkv, kvh = qi % a.Hkv;
+    // the group whose blocks include b: largest g with block_start[g] <= b (workgroup-uniform)
+    int lo = 0, hi = a.NG;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (ld_uniform(a.block_start + mid) <= b) lo = mid; else hi = mid;
+    }
+    const int first_block = ld_uniform(a.block_start + lo);
+    const int nblocks = ld_uniform(a.block_start + lo + 1) - first_block;
+    const int rb = nblocks - 1 - (b - first_block);   // last block (most keys) first
+    prefill_item(a, lo, rb * kQB, kvh, lds, bad_page);
+  }
+  if (bad_page) atomicOr(&a.counters[kPfFlags], MARL_FLAG_BAD_PAGE);
+}
+
+// Scatter of a prompt chunk's keys and values into the group's pages: one workgroup of 128
+// threads per (query token, KV head), as the decode append does for one token per sequence.
+__global__ __launch_bounds__(kD) void kv_write_prompt_kernel(PrefillArgs a) {
+  const int tok = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+  const int c = threadIdx.x;
+  // group of this token: largest g with q_start[g] <= tok
+  int lo = 0, hi = a.NG;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.q_start[mid] <= tok) lo = mid; else hi = mid;
+  }
+  int flag = 0;
+  const int n = group_tokens(a, lo, flag);
+  const int tau = tok - a.q_start[lo];
+  int page = -1, pos = 0;
+  if (tau >= 0 && tau < n) {
+    pos = a.q_pos0[lo] + tau;
+    page = a.prefix_table[(size_t)lo * a.max_pp + (pos >> 4)];
+    if ((unsigned)page >= (unsigned)a.num_pages) { flag |= MARL_FLAG_BAD_PAGE; page = -1; }
+  } else if (!flag) {
+    flag = MARL_FLAG_BAD_GROUP;   // a token no group claims (q_start not a partition of the rows)
+  }
+  if (page >= 0) {
+    const int slot = pos & (kPage - 1);
+    const size_t blk = ((size_t)page * a.Hkv + kvh) * (kPage * kD);
+    const uint16_t* kn = a.k_new + ((size_t)tok * a.Hkv + kvh) * kD;
+    const uint16_t* vn = a.v_new + ((size_t)tok * a.Hkv + kvh) * kD;
+    a.v_pages_w[blk + (size_t)c * kPage + slot] = vn[c];
+    if (c < 16)
+      *reinterpret_cast<u32x4*>(a.k_pages_w + blk + (size_t)slot * kD + c * 8) =
+          *reinterpret_cast<const u32x4*>(kn + c * 8);
+  }
+  if (flag && c == 0 && a.flags) atomicOr(a.flags, flag);
+}
+
+}  // namespace
+
+int prefill_rows_per_block() { return kQB; }
+
+int prefill_blocks_per_cu() {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, prefill_kernel, kPfThreads, 0) != hipSuccess || n < 1) n = 1;
+  return n;
+}
+
+hipError_t launch_prefill(const PrefillArgs& a, int grid, hipStream_t st) {
+  hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreadsPf), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_write_prompt(const PrefillArgs& a, hipStream_t st) {
+  if (a.NT == 0 || a.NG == 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_write_prompt_kernel, dim3((unsigned)a.NT * a.Hkv), dim3(kD), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace marl

@@ -361,3 +361,79 @@ def build_logprob_inputs(rows: int, vocab: int, sigma: float, seed: int, device=
 def bf16_bits(t: torch.Tensor) -> np.ndarray:
     """The raw 16-bit patterns of a bf16 tensor as a uint16 numpy array (CPU copy)."""
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+# --------------------------------------------------------------------------------------
+# prompt (prefill) inputs
+# --------------------------------------------------------------------------------------
+@dataclass
+class PrefillInputs:
+    Hq: int
+    Hkv: int
+    num_pages: int
+    q: torch.Tensor                    # bf16 [NT, Hq, D]: the query tokens of all groups, group after group
+    k_new: torch.Tensor                # bf16 [NT, Hkv, D]: keys of the same tokens (for the prompt scatter)
+    v_new: torch.Tensor                # bf16 [NT, Hkv, D]
+    k_pages: torch.Tensor              # bf16 [num_pages, Hkv, PAGE, D]; every position < pos0 + n holds data
+    v_pages: torch.Tensor              # bf16 [num_pages, Hkv, D, PAGE]
+    prefix_block_table: torch.Tensor   # int32 [NG, max_prefix_pages]
+    q_start: torch.Tensor              # int32 [NG + 1]
+    q_pos0: torch.Tensor               # int32 [NG]
+    scale: float
+
+    @property
+    def num_tokens(self): return int(self.q.shape[0])
+    @property
+    def num_groups(self): return int(self.q_pos0.shape[0])
+
+    def to(self, device) -> "PrefillInputs":
+        kw = {f: getattr(self, f).to(device) for f in ("q", "k_new", "v_new", "k_pages", "v_pages",
+                                                       "prefix_block_table", "q_start", "q_pos0")}
+        return replace(self, **kw)
+
+    def causal_pairs(self) -> int:
+        """Number of (query token, visible key) pairs: the unit of the operation's work."""
+        n = np.diff(self.q_start.cpu().numpy().astype(np.int64))
+        p0 = self.q_pos0.cpu().numpy().astype(np.int64)
+        return int((n * p0 + n * (n + 1) // 2).sum())
+
+
+def build_prefill_inputs(Hq: int, Hkv: int, chunk_lens: Sequence[int], pos0: Sequence[int], device="cpu",
+                         seed: int = 0, poison: bool = True, spare_frac: float = 0.05,
+                         extra_cols: int = 0) -> PrefillInputs:
+    """Group g brings chunk_lens[g] query tokens at positions pos0[g] .. of its prompt.  Pages are
+    a random permutation; every cache position below pos0[g] + chunk_lens[g] holds N(0,1) data
+    (so attention can be run without the scatter), everything else NaN when `poison`."""
+    rng = np.random.default_rng(seed)
+    n = np.asarray(chunk_lens, dtype=np.int64)
+    p0 = np.asarray(pos0, dtype=np.int64)
+    NG = len(n)
+    total = p0 + n
+    npages = (total + PAGE - 1) // PAGE
+    used_pages = int(npages.sum())
+    num_pages = max(1, int(math.ceil(used_pages * (1.0 + spare_frac))) + (1 if spare_frac > 0 else 0))
+    perm = rng.permutation(num_pages).astype(np.int32)
+    mpp = max(1, int(npages.max()) if NG else 1) + extra_cols
+    ptab = np.full((NG, mpp), -1, dtype=np.int32)
+    cur = 0
+    for g in range(NG):
+        ptab[g, :npages[g]] = perm[cur:cur + npages[g]]
+        cur += int(npages[g])
+    used = np.zeros(num_pages, dtype=bool)
+    used[perm[:cur]] = True
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    NT = int(n.sum())
+    q = randn_bf16((NT, Hq, D), 1.0, gen, device)
+    k_new = randn_bf16((NT, Hkv, D), 1.0, gen, device)
+    v_new = randn_bf16((NT, Hkv, D), 1.0, gen, device)
+    k_pages = randn_bf16((num_pages, Hkv, PAGE, D), 1.0, gen, device)
+    v_pages = randn_bf16((num_pages, Hkv, D, PAGE), 1.0, gen, device)
+    if poison:
+        empty = np.zeros((0, 1), dtype=np.int32)
+        poison_unused(k_pages, v_pages, ptab, empty, total, np.zeros(0, dtype=np.int64), used)
+    q_start = np.zeros(NG + 1, dtype=np.int32)
+    q_start[1:] = np.cumsum(n)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+    return PrefillInputs(Hq, Hkv, num_pages, q, k_new, v_new, k_pages, v_pages, t(ptab), t(q_start),
+                         t(p0.astype(np.int32)), scale=1.0 / math.sqrt(D))
