@@ -193,6 +193,32 @@ def main():
             tot += ev0.elapsed_time(ev1)
     res["sample_tokens"] = {"us_per_call": tot / 10 * 1e3, "rows": w.num_seqs,
                             "GBps": w.num_seqs * vocab * 2 / (tot / 10 * 1e-3) / 1e9}
+    # prompt (prefill) attention over the workload's prompts: the step that creates the shared
+    # prefixes; dense causal MFMA work, reported against the bf16 matrix peak
+    del s_ws, uniforms
+    pf = I.build_prefill_inputs(w.Hq, w.Hkv, attn.prefix_lens.cpu().tolist(), [0] * w.num_groups, device=dev,
+                                seed=w.seed, poison=False)
+    pshape, pws, pout = B.prepare_prefill(pf, B.MARL_OUT_BF16)
+    pflags = torch.zeros(1, dtype=torch.int32, device=dev)
+    t_attn = t_write = 0.0
+    for it in range(7):
+        ev0.record()
+        B.marl_kv_write_prompt(pshape, pf.k_new, pf.v_new, pf.k_pages, pf.v_pages, pf.prefix_block_table,
+                               pf.q_start, pf.q_pos0, pflags)
+        ev1.record()
+        ev2 = torch.cuda.Event(enable_timing=True)
+        B.run_prefill(pf, pshape, pws, pout)
+        ev2.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            t_write += ev0.elapsed_time(ev1)
+            t_attn += ev1.elapsed_time(ev2)
+    assert int(pflags.item()) == 0 and B.marl_attn_read_flags(pws) == 0
+    pf_flops = pf.causal_pairs() * w.Hq * 4 * 128
+    res["prefill"] = {"ms_per_call": t_attn / 5, "prompt_tokens": pf.num_tokens, "TFLOPps": pf_flops / (t_attn / 5 * 1e-3) / 1e12,
+                      "frac_of_bf16_mfma_peak": pf_flops / (t_attn / 5 * 1e-3) / 1e12 / 2500.0,
+                      "kv_write_prompt_us": t_write / 5 * 1e3}
+    del pf, pws, pout
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
     print(json.dumps(res))

@@ -258,9 +258,10 @@ int marl_prefill_attn(const marl_prefill_shape* shape, void* workspace, size_t w
  * Scatter of prompt keys / values into the pages: token q_start[g] + tau of k_new / v_new
  * (bf16 [num_tokens, Hkv, 128]) goes to position q_pos0[g] + tau of group g, i.e. page
  * prefix_block_table[g][pos / 16], slot pos % 16 (K [page][kv_head][slot][128],
- * V [page][kv_head][128][slot]).  Tokens that do not fit, belong to no group or point to a
- * page out of range are skipped and flagged in *flags (device int32, may be NULL; OR-ed, the
- * caller zeroes it).  Bit-exact data movement.
+ * V [page][kv_head][128][slot]).  Skipped and flagged in *flags (device int32, may be NULL;
+ * OR-ed, the caller zeroes it): the tokens of a group that do not fit its table row
+ * (MARL_FLAG_LEN_CLAMPED), a group with an inconsistent q_start / q_pos0 entry
+ * (MARL_FLAG_BAD_GROUP), a page id out of range (MARL_FLAG_BAD_PAGE).  Bit-exact data movement.
  */
 int marl_kv_write_prompt(const marl_prefill_shape* shape, const void* k_new, const void* v_new,
                          void* k_pages, void* v_pages, const int32_t* prefix_block_table,

@@ -452,8 +452,15 @@ int check_prefill_shape(const marl_prefill_shape* s) {
   return MARL_OK;
 }
 constexpr size_t kPrefillHeaderBytes = 256;   // counters
+size_t prefill_start_bytes(const marl_prefill_shape* s) {
+  return align_up(((size_t)s->num_groups + 1) * sizeof(int32_t), 256);
+}
+long prefill_max_blocks(const marl_prefill_shape* s) {   // row blocks of all groups, upper bound
+  const long R = s->num_q_heads / s->num_kv_heads;
+  return (long)s->num_tokens * R / marl::prefill_rows_per_block() + s->num_groups;
+}
 size_t prefill_ws_bytes(const marl_prefill_shape* s) {
-  return kPrefillHeaderBytes + align_up(((size_t)s->num_groups + 1) * sizeof(int32_t), 256);
+  return kPrefillHeaderBytes + prefill_start_bytes(s) + align_up((size_t)prefill_max_blocks(s) * sizeof(int2), 256);
 }
 void fill_prefill_args(const marl_prefill_shape* s, marl::PrefillArgs& a) {
   memset(&a, 0, sizeof a);
@@ -503,13 +510,16 @@ int marl_prefill_attn(const marl_prefill_shape* shape, void* workspace, size_t w
   a.out = out;
   a.counters = static_cast<int32_t*>(workspace);
   a.block_start = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + kPrefillHeaderBytes);
+  a.items = reinterpret_cast<int2*>(static_cast<char*>(workspace) + kPrefillHeaderBytes + prefill_start_bytes(shape));
+  if (prefill_max_blocks(shape) >= (1L << 28)) return MARL_UNSUPPORTED;
+  a.max_blocks = (int32_t)prefill_max_blocks(shape);
   a.scale = scale;
   int dev = 0, cus = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return hip_fail(e, "device query");
   // no more workgroups than the shape can have row blocks
-  const long max_items = ((long)a.NT * a.R / marl::prefill_rows_per_block() + a.NG) * a.Hkv;
+  const long max_items = prefill_max_blocks(shape) * a.Hkv;
   long grid = (long)cus * marl::prefill_blocks_per_cu();
   if (grid > max_items) grid = max_items;
   if (grid < 1) grid = 1;
@@ -527,7 +537,8 @@ int marl_kv_write_prompt(const marl_prefill_shape* shape, const void* k_new, con
   if (!k_new || !v_new || !k_pages || !v_pages || !prefix_block_table || !q_start || !q_pos0)
     return MARL_INVALID_ARG;
   if (shape->max_prefix_pages < 1) return MARL_INVALID_ARG;
-  if ((long)shape->num_tokens * shape->num_kv_heads >= (1L << 31)) return MARL_UNSUPPORTED;
+  // one workgroup per (group, KV head, table column)
+  if ((long)shape->num_groups * shape->num_kv_heads * shape->max_prefix_pages >= (1L << 31)) return MARL_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(k_new) % 16 != 0 || reinterpret_cast<uintptr_t>(k_pages) % 16 != 0)
     return MARL_INVALID_ARG;
   marl::PrefillArgs a;

@@ -112,13 +112,14 @@ struct PrefillArgs {
   void* out;                    // [NT][Hq][128]
   int32_t* counters;            // workspace header
   int32_t* block_start;         // [NG + 1] running number of row blocks
+  int2* items;                  // [blocks] (group, first row of the block)
   // the prompt scatter only:
   const uint16_t* k_new;        // [NT][Hkv][128]
   const uint16_t* v_new;
   uint16_t* k_pages_w;
   uint16_t* v_pages_w;
   int32_t* flags;
-  int32_t NT, NG, Hq, Hkv, R, num_pages, max_pp, out_dtype;
+  int32_t NT, NG, Hq, Hkv, R, num_pages, max_pp, out_dtype, max_blocks;
   float scale;
 };
 int prefill_rows_per_block();

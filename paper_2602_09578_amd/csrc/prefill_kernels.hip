@@ -17,8 +17,8 @@
 // written directly (no partials, no merge).
 //
 // Work distribution: a one-workgroup plan kernel turns q_start into the running number of
-// row blocks per group; workgroups then draw (block, KV head) indices from a counter and find
-// the group by bisection.  Inside a group the blocks are taken last-first (most keys first).
+// row blocks per group and lists the blocks (group, first row), inside a group last-first
+// (most keys first); workgroups then draw (block, KV head) indices from a counter.
 #include "marl_internal.h"
 #include "wave_ops.h"
 
@@ -60,25 +60,42 @@ __device__ __forceinline__ int group_tokens(const PrefillArgs& a, int g, int& fl
 }
 
 __global__ __launch_bounds__(kPlanThreadsPf) void prefill_plan_kernel(PrefillArgs a) {
-  __shared__ int part[kPlanThreadsPf];
-  __shared__ int carry, flags_all;
+  __shared__ long long part[kPlanThreadsPf];   // 64-bit: inconsistent inputs must not wrap the sums
+  __shared__ long long carry;
+  __shared__ int flags_all, end_all;
   const int tid = threadIdx.x;
   int flag = 0;
-  if (tid == 0) carry = flags_all = 0;
+  if (tid == 0) { carry = 0; flags_all = end_all = 0; }
   __syncthreads();
   for (int g0 = 0; g0 < a.NG; g0 += kPlanThreadsPf) {
     const int g = g0 + tid;
     int nb = 0;
     if (g < a.NG) nb = (int)(((long)group_tokens(a, g, flag) * a.R + kQB - 1) / kQB);
+    // groups that overlap in q could ask for more blocks than the workspace was sized for
+    // (its bound assumes they share no rows): such a group is dropped
+    if (nb > a.max_blocks) { nb = 0; flag |= MARL_FLAG_BAD_GROUP; }
     part[tid] = nb;
     __syncthreads();
     for (int d = 1; d < kPlanThreadsPf; d <<= 1) {   // inclusive scan
-      const int v = tid >= d ? part[tid - d] : 0;
+      const long long v = tid >= d ? part[tid - d] : 0;
       __syncthreads();
       part[tid] += v;
       __syncthreads();
     }
-    if (g < a.NG) a.block_start[g] = carry + part[tid] - nb;
+    if (g < a.NG) {
+      const long long first64 = carry + part[tid] - nb;
+      int first = a.max_blocks;
+      if (first64 + nb > a.max_blocks) {   // as above; every later group then fails this test too
+        flag |= MARL_FLAG_BAD_GROUP;
+        nb = 0;
+      } else {
+        first = (int)first64;
+        atomicMax(&end_all, first + nb);
+      }
+      a.block_start[g] = first;
+      // the group's work items, last row block (most keys) first
+      for (int k = 0; k < nb; ++k) a.items[first + k] = make_int2(g, (nb - 1 - k) * kQB);
+    }
     __syncthreads();
     if (tid == kPlanThreadsPf - 1) carry += part[tid];
     __syncthreads();
@@ -86,7 +103,7 @@ __global__ __launch_bounds__(kPlanThreadsPf) void prefill_plan_kernel(PrefillArg
   if (flag) atomicOr(&flags_all, flag);
   __syncthreads();
   if (tid == 0) {
-    a.block_start[a.NG] = carry;
+    a.block_start[a.NG] = end_all;   // the accepted groups' blocks are exactly [0, end_all)
     a.counters[kPfCursor] = 0;
     a.counters[kPfFlags] = flags_all;   // the attention kernel may add MARL_FLAG_BAD_PAGE
   }
@@ -152,45 +169,43 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
 
   const int nsteps = (tok_end + kBlockTok - 1) / kBlockTok;
   const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
-  const char* dummy = reinterpret_cast<const char*>(a.q);   // any valid 16 bytes
 
+  // Page ids of step n (wave-uniform scalar loads).  A step past the end repeats the last one:
+  // its loads fetch valid bytes that nobody uses, so the loop needs no conditional loads and
+  // every wait knows how many younger loads are in flight.
   auto load_ids = [&](int n, int& p0, int& p1) {
-    p0 = -1;
-    p1 = -1;
-    if (n < nsteps) {
-      const int t = n * kBlockTok;
-      p0 = ld_uniform(table_row + (t >> 4));
-      p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
-      if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
-      if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
-    }
+    const int t = min(n, nsteps - 1) * kBlockTok;
+    p0 = ld_uniform(table_row + (t >> 4));
+    p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
+    if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
+    if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
   };
   // A step is 1024 16-byte vectors: K of page 0, K of page 1, V of page 0, V of page 1 (256
-  // each, contiguous in memory); thread tid fetches vectors tid + k * threads.  K lands in LDS
-  // as 32 token rows of 256 B with the 16-byte chunk index XOR-ed with a key of the row, V as
+  // each, contiguous in memory); thread tid fetches vectors tid + k * threads, so which of the
+  // four regions a load belongs to is the same for a whole wave: the page's base address is
+  // scalar arithmetic and a lane adds only its fixed 32-bit offset.  K lands in LDS as 32 token
+  // rows of 256 B with the 16-byte chunk index XOR-ed with a key of the row, V as
   // [page][channel][2 halves of 8 slots] with the unit index XOR-ed with (unit >> 3) & 1, so
   // that the 8 lanes of one operand read hit 8 different bank groups.
-  const char* src_base[kLoads];
-  int lds_off[kLoads];
-  bool second_page[kLoads];
+  static_assert(kNW % 4 == 0, "a wave's 64 vectors must lie in one 256-vector region");
+  const int w = tid & 255;
+  const uint32_t lane_off = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)w * 16;
+  int region[kLoads], lds_off[kLoads];
 #pragma unroll
   for (int k = 0; k < kLoads; ++k) {
-    const int v = tid + k * kNW * 64;
-    const int region = v >> 8, w = v & 255;
-    second_page[k] = region & 1;
-    const bool is_v = region >> 1;
-    src_base[k] = reinterpret_cast<const char*>(is_v ? a.v_pages : a.k_pages) + (size_t)kvh * (kPage * kD * 2) + w * 16;
+    region[k] = k * (kNW / 4) + (wave >> 2);      // = (tid + k * threads) >> 8, wave-uniform
+    const bool is_v = region[k] >> 1;
     const int slot = w >> 4;
-    lds_off[k] = is_v ? 2 * kBlockTok * kD + (region & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
-                      : ((region & 1) * 16 + slot) * 256 + (((w & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)) << 4);
+    lds_off[k] = is_v ? 2 * kBlockTok * kD + (region[k] & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
+                      : ((region[k] & 1) * 16 + slot) * 256 + (((w & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)) << 4);
   }
-  // unconditional loads (a step past the end re-reads 16 valid bytes nobody uses): every wait
-  // in the loop then knows how many younger loads are in flight
   auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
-    const bool ok = p0 >= 0;
 #pragma unroll
-    for (int k = 0; k < kLoads; ++k)
-      st[k] = *reinterpret_cast<const u32x4*>(ok ? src_base[k] + (size_t)(second_page[k] ? p1 : p0) * page_bytes : dummy);
+    for (int k = 0; k < kLoads; ++k) {
+      const char* base = reinterpret_cast<const char*>((region[k] >> 1) ? a.v_pages : a.k_pages) +
+                         (size_t)((region[k] & 1) ? p1 : p0) * page_bytes;
+      st[k] = *reinterpret_cast<const u32x4*>(base + lane_off);
+    }
   };
   auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
 #pragma unroll
@@ -202,7 +217,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   auto compute = [&](int n, const char* buf) {
     const int t0 = n * kBlockTok;
     const bool ragged = t0 + kBlockTok > tok_end;   // workgroup-uniform; only the last step
-    u32x4 pb[kMT];
+    u32x4 pb[kMT];   // set and used only for the tiles this step touches
     u32x4 kr[2][4];
 #pragma unroll
     for (int T = 0; T < 2; ++T)
@@ -211,7 +226,6 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
         kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ (i & 7)) << 4));
 #pragma unroll
     for (int qt = 0; qt < kMT; ++qt) {
-      pb[qt] = u32x4{0u, 0u, 0u, 0u};
       if (t0 < tile_hi[qt]) {   // wave-uniform: some row of the tile sees a token of this step
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -336,63 +350,80 @@ void prefill_kernel(PrefillArgs a) {
   __shared__ int next_item;
   const int n_work = a.block_start[a.NG] * a.Hkv;
   int bad_page = 0;
-  for (bool first = true;; first = false) {
-    int qi = blockIdx.x;
-    if (!first) {
-      if (threadIdx.x == 0) next_item = gridDim.x + atomicAdd(&a.counters[kPfCursor], 1);
-      __syncthreads();
-      qi = next_item;
-      __syncthreads();
-    }
-    if (qi >= n_work) break;
-    const int b = qi / a.Hkv, kvh = qi % a.Hkv;
-    // the group whose blocks include b: largest g with block_start[g] <= b (workgroup-uniform)
-    int lo = 0, hi = a.NG;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (ld_uniform(a.block_start + mid) <= b) lo = mid; else hi = mid;
-    }
-    const int first_block = ld_uniform(a.block_start + lo);
-    const int nblocks = ld_uniform(a.block_start + lo + 1) - first_block;
-    const int rb = nblocks - 1 - (b - first_block);   // last block (most keys) first
-    prefill_item(a, lo, rb * kQB, kvh, lds, bad_page);
+  // The first item is the block index; later ones come from the counter, drawn when the
+  // workgroup is free (drawing the next index while an item runs measured 2-5 % slower).
+  int qi = blockIdx.x;
+  while (qi < n_work) {
+    const int2 it = a.items[qi / a.Hkv];
+    prefill_item(a, it.x, it.y, qi % a.Hkv, lds, bad_page);
+    // prefill_item ends with a workgroup barrier after its last LDS use
+    if (threadIdx.x == 0) next_item = gridDim.x + atomicAdd(&a.counters[kPfCursor], 1);
+    __syncthreads();
+    qi = next_item;
+    __syncthreads();
   }
   if (bad_page) atomicOr(&a.counters[kPfFlags], MARL_FLAG_BAD_PAGE);
 }
 
-// Scatter of a prompt chunk's keys and values into the group's pages: one workgroup of 128
-// threads per (query token, KV head), as the decode append does for one token per sequence.
+// Scatter of a prompt chunk's keys and values into the group's pages.  One workgroup of 128
+// threads per (group, KV head, column of the group's table row); a column the chunk does not
+// touch exits at once.  The key rows of a page are contiguous (4 KB): 16-byte copies.  Values
+// are stored channel-major, so thread c collects channel c of the page's 16 tokens and writes
+// its 32 bytes with two stores when the chunk covers the whole page, else slot by slot.
 __global__ __launch_bounds__(kD) void kv_write_prompt_kernel(PrefillArgs a) {
-  const int tok = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+  const int col = blockIdx.x % a.max_pp;
+  const int gk = blockIdx.x / a.max_pp;
+  const int g = gk / a.Hkv, kvh = gk % a.Hkv;
   const int c = threadIdx.x;
-  // group of this token: largest g with q_start[g] <= tok
-  int lo = 0, hi = a.NG;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.q_start[mid] <= tok) lo = mid; else hi = mid;
-  }
   int flag = 0;
-  const int n = group_tokens(a, lo, flag);
-  const int tau = tok - a.q_start[lo];
-  int page = -1, pos = 0;
-  if (tau >= 0 && tau < n) {
-    pos = a.q_pos0[lo] + tau;
-    page = a.prefix_table[(size_t)lo * a.max_pp + (pos >> 4)];
-    if ((unsigned)page >= (unsigned)a.num_pages) { flag |= MARL_FLAG_BAD_PAGE; page = -1; }
-  } else if (!flag) {
-    flag = MARL_FLAG_BAD_GROUP;   // a token no group claims (q_start not a partition of the rows)
+  const int n = group_tokens(a, g, flag);
+  const int pos0 = a.q_pos0[g];
+  const int lo = max(pos0, col * kPage), hi = min(pos0 + n, (col + 1) * kPage);   // positions to write
+  if (col == 0 && kvh == 0 && c == 0 && flag && a.flags) atomicOr(a.flags, flag);
+  if (flag & MARL_FLAG_BAD_GROUP) return;
+  if (lo >= hi) return;
+  const int page = a.prefix_table[(size_t)g * a.max_pp + col];
+  if ((unsigned)page >= (unsigned)a.num_pages) {
+    if (kvh == 0 && c == 0 && a.flags) atomicOr(a.flags, MARL_FLAG_BAD_PAGE);
+    return;
   }
-  if (page >= 0) {
-    const int slot = pos & (kPage - 1);
-    const size_t blk = ((size_t)page * a.Hkv + kvh) * (kPage * kD);
-    const uint16_t* kn = a.k_new + ((size_t)tok * a.Hkv + kvh) * kD;
-    const uint16_t* vn = a.v_new + ((size_t)tok * a.Hkv + kvh) * kD;
-    a.v_pages_w[blk + (size_t)c * kPage + slot] = vn[c];
-    if (c < 16)
-      *reinterpret_cast<u32x4*>(a.k_pages_w + blk + (size_t)slot * kD + c * 8) =
-          *reinterpret_cast<const u32x4*>(kn + c * 8);
+  const size_t blk = ((size_t)page * a.Hkv + kvh) * (kPage * kD);                 // elements
+  const size_t tok0 = (size_t)a.q_start[g] + (col * kPage - pos0);                // token of slot 0 (may be "negative")
+  const size_t row_stride = (size_t)a.Hkv * kD;
+  // keys: 16 slots x 16 chunks of 16 bytes, two per thread
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int v = c + k * kD;
+    const int slot = v >> 4, chunk = v & 15;
+    const int pos = col * kPage + slot;
+    if (pos >= lo && pos < hi)
+      *reinterpret_cast<u32x4*>(a.k_pages_w + blk + (size_t)slot * kD + chunk * 8) =
+          *reinterpret_cast<const u32x4*>(a.k_new + (tok0 + slot) * row_stride + (size_t)kvh * kD + chunk * 8);
   }
-  if (flag && c == 0 && a.flags) atomicOr(a.flags, flag);
+  // values: channel c of every slot
+  uint16_t vals[kPage];
+#pragma unroll
+  for (int slot = 0; slot < kPage; ++slot) {
+    const int pos = col * kPage + slot;
+    vals[slot] = (pos >= lo && pos < hi) ? a.v_new[(tok0 + slot) * row_stride + (size_t)kvh * kD + c] : (uint16_t)0;
+  }
+  uint16_t* vdst = a.v_pages_w + blk + (size_t)c * kPage;
+  if (hi - lo == kPage) {
+    u32x4 w0, w1;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      w0[d] = (uint32_t)vals[2 * d] | ((uint32_t)vals[2 * d + 1] << 16);
+      w1[d] = (uint32_t)vals[8 + 2 * d] | ((uint32_t)vals[8 + 2 * d + 1] << 16);
+    }
+    *reinterpret_cast<u32x4*>(vdst) = w0;
+    *reinterpret_cast<u32x4*>(vdst + 8) = w1;
+  } else {
+#pragma unroll
+    for (int slot = 0; slot < kPage; ++slot) {
+      const int pos = col * kPage + slot;
+      if (pos >= lo && pos < hi) vdst[slot] = vals[slot];
+    }
+  }
 }
 
 }  // namespace
@@ -415,7 +446,7 @@ hipError_t launch_prefill(const PrefillArgs& a, int grid, hipStream_t st) {
 
 hipError_t launch_kv_write_prompt(const PrefillArgs& a, hipStream_t st) {
   if (a.NT == 0 || a.NG == 0) return hipSuccess;
-  hipLaunchKernelGGL(kv_write_prompt_kernel, dim3((unsigned)a.NT * a.Hkv), dim3(kD), 0, st, a);
+  hipLaunchKernelGGL(kv_write_prompt_kernel, dim3((unsigned)a.NG * a.Hkv * a.max_pp), dim3(kD), 0, st, a);
   return hipGetLastError();
 }
 

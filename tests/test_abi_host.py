@@ -148,16 +148,16 @@ def test_prefill_argument_errors_without_gpu():
     mk = lambda **kw: B.make_prefill_shape(**{**dict(num_tokens=64, num_groups=2, num_q_heads=28, num_kv_heads=4,
                                                      num_pages=16, max_prefix_pages=4), **kw})
     n = ctypes.c_size_t(0)
-    assert lib.marl_prefill_workspace_bytes(ctypes.byref(mk()), ctypes.byref(n)) == 0 and n.value == 512
+    assert lib.marl_prefill_workspace_bytes(ctypes.byref(mk()), ctypes.byref(n)) == 0 and n.value == 768   # header + starts + (64*7/128 + 2) items
     assert lib.marl_prefill_workspace_bytes(ctypes.byref(mk(num_q_heads=30)), ctypes.byref(n)) == -1
     assert lib.marl_prefill_workspace_bytes(ctypes.byref(mk(head_dim=64)), ctypes.byref(n)) == -2
     assert lib.marl_prefill_workspace_bytes(ctypes.byref(mk(num_q_heads=68)), ctypes.byref(n)) == -2   # 17 heads per KV head
     at = lambda sh, ws, nbytes, q, scale=1.0: lib.marl_prefill_attn(ctypes.byref(sh), ws, nbytes, q, p, p, p, p, p,
                                                                      ctypes.c_float(scale), p, None)
-    assert at(mk(), p, 512, None) == -1 and at(mk(), None, 512, p) == -1
-    assert at(mk(), p, 512, p, float("nan")) == -1
-    assert at(mk(), p, 256, p) == -3
-    assert at(mk(max_prefix_pages=0), p, 512, p) == -1
+    assert at(mk(), p, 768, None) == -1 and at(mk(), None, 768, p) == -1
+    assert at(mk(), p, 768, p, float("nan")) == -1
+    assert at(mk(), p, 512, p) == -3
+    assert at(mk(max_prefix_pages=0), p, 768, p) == -1
     assert at(mk(num_tokens=0), None, 0, None) == 0              # nothing to do
     wr = lambda sh, k_new: lib.marl_kv_write_prompt(ctypes.byref(sh), k_new, p, p, p, p, p, p, None, None)
     assert wr(mk(), None) == -1 and wr(mk(num_groups=0), None) == 0 and wr(mk(page_size=32), p) == -2

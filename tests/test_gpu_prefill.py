@@ -184,3 +184,16 @@ def test_last_prompt_row_equals_the_decode_call_on_the_same_cache():
                        torch.arange(2, dtype=torch.int32, device="cuda"), inp.scale, dout)
     torch.cuda.synchronize()
     assert float((out[last] - dout).abs().max()) < 2e-3
+
+
+def test_overlapping_groups_cannot_overrun_the_item_list():
+    # three groups that all claim rows 0..299 of a 300-row q: the workspace is sized for groups
+    # that share no rows, so the ones that do not fit are dropped and flagged
+    from dataclasses import replace
+    a = I.build_prefill_inputs(28, 4, [300, 0, 0], [0, 0, 0], seed=12, poison=False)
+    tab = a.prefix_block_table[0:1].expand(3, -1).contiguous()
+    qs = torch.tensor([0, 300, 0, 300], dtype=torch.int32)       # group 1 is inconsistent, group 2 overlaps group 0
+    # q_start[1..2] = (300, 0): negative count -> flag 1; group 2 = rows 0..299 again
+    got = run_gpu(replace(a, prefix_block_table=tab, q_start=qs), B.MARL_OUT_F32, expect_flags=B.FLAG_BAD_GROUP)
+    want, want_abs = reference(a)
+    assert (np.abs(got - want) <= 1e-3 + 2.0 ** -8 * want_abs).all()
