@@ -287,6 +287,69 @@ int marl_grpo_advantages(const float* rewards, const int32_t* group_start,
                          void* stream);
 
 /*
+ * Hierarchical load balancing of rollout requests (Section 5.2 of the paper), as a host-side,
+ * step-driven simulation that yields the per-step batch composition of every inference
+ * instance (the sequences one marl_decode_attn call of that instance would cover).  All
+ * pointers are HOST pointers; nothing here touches the GPU.  A handle is not thread-safe.
+ *
+ * Model.  Agents own inference instances (global ids 0.., handed out agent after agent).  An
+ * instance holds a FIFO list of unfinished requests; its load is the length of that list; the
+ * first slots_per_instance of them run (one token per step), the rest wait.
+ *   submit: the request goes to the agent's active instance with the smallest load (ties: the
+ *     smallest instance id), found with a min-heap (intra-agent balancing).
+ *   step:  (1) instances whose migration has finished join their new agent with an empty list;
+ *     (2) every active instance emits one token for each running request; requests that reach
+ *     their length complete (done_step = the step counter before it is advanced) and leave;
+ *     (3) the step counter advances; if it is a multiple of poll_interval, the agents' waiting
+ *     queues q_a (sum over active instances of max(0, load - slots)) are compared: receiver =
+ *     the longest queue (ties: smallest agent id), donor = the shortest queue (ties: most active
+ *     instances, then smallest id).  If q_receiver - q_donor > delta, then
+ *     min(ceil(difference / slots_per_instance), donor's active instances - 1) instances move:
+ *     each time the donor's least-loaded instance (ties: smallest id) is detached, its
+ *     requests are re-submitted in order to the donor's remaining instances (progress kept),
+ *     and it joins the receiver migration_delay steps later (inter-agent balancing).
+ * Readings of the paper, which states the rules only in prose: "queue length" is the number of
+ * waiting (not running) requests; the number of instances moved is the queue difference in
+ * units of one instance's slots (with slots_per_instance = 1 this is the paper's "difference in
+ * queue lengths"); a moved instance serves only requests submitted after it joins; its old
+ * requests are re-queued on the donor.  The paper sets delta = 5 (Section 8.1).
+ */
+typedef struct marl_balancer marl_balancer;
+typedef struct {
+  int32_t num_agents;
+  int32_t delta;               /* disparity threshold, >= 0 */
+  int32_t slots_per_instance;  /* requests an instance decodes concurrently, >= 1 */
+  int32_t poll_interval;       /* steps between inter-agent polls, >= 1 */
+  int32_t migration_delay;     /* steps a moved instance is offline, >= 0 */
+} marl_balancer_config;
+typedef struct {
+  int64_t now;                 /* steps taken */
+  int64_t submitted, completed;
+  int64_t migrations;          /* instances moved so far */
+} marl_balancer_stats;
+/* instances_per_agent: [num_agents], each >= 1.  *out receives the handle. */
+int marl_balancer_create(const marl_balancer_config* cfg, const int32_t* instances_per_agent,
+                         marl_balancer** out);
+void marl_balancer_destroy(marl_balancer* b);
+/* request_id >= 0 and unused so far, gen_len >= 1 tokens; *instance (may be NULL) receives the
+ * chosen instance. */
+int marl_balancer_submit(marl_balancer* b, int32_t agent, int32_t request_id, int32_t gen_len,
+                         int32_t* instance);
+int marl_balancer_step(marl_balancer* b, marl_balancer_stats* stats /* may be NULL */);
+/* any of the output pointers may be NULL */
+int marl_balancer_agent_state(const marl_balancer* b, int32_t agent, int32_t* active_instances,
+                              int64_t* waiting_requests, int64_t* assigned_requests);
+/* The requests the instance will decode in the next step, in list order, with the tokens each
+ * has generated so far.  *owner = its agent, or -1 while it migrates.  *count is always set;
+ * MARL_WORKSPACE_TOO_SMALL if it exceeds capacity (then nothing else is written). */
+int marl_balancer_instance_batch(const marl_balancer* b, int32_t instance, int32_t* owner,
+                                 int32_t* request_ids, int32_t* generated, int32_t capacity,
+                                 int32_t* count);
+/* *instance = where the request is now (-1 once complete), *done_step = -1 while unfinished */
+int marl_balancer_request_state(const marl_balancer* b, int32_t request_id, int32_t* instance,
+                                int32_t* generated, int64_t* done_step);
+
+/*
  * Per-kernel timing of marl_decode_attn / marl_token_logprobs calls (for benchmarks).
  * After marl_profile_begin(max_calls) every call records HIP events around each of its
  * kernels on the call's stream (no synchronisation).  marl_profile_end() synchronises the

@@ -46,6 +46,14 @@ class PrefillShape(ctypes.Structure):
         "num_pages", "max_prefix_pages", "out_dtype", "reserved")]
 
 
+class BalancerConfig(ctypes.Structure):
+    _fields_ = [(n, I32) for n in ("num_agents", "delta", "slots_per_instance", "poll_interval", "migration_delay")]
+
+
+class BalancerStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("now", "submitted", "completed", "migrations")]
+
+
 class MarlError(RuntimeError):
     def __init__(self, status: int, where: str, detail: str = ""):
         self.status = status
@@ -85,6 +93,15 @@ def load_library(build_if_missing: bool = True):
     lib.marl_sample_tokens.argtypes = [VP, VP, ctypes.c_float, VP, VP, I32, I32, VP, SZ, VP]
     lib.marl_sample_workspace_bytes.restype = lib.marl_sample_tokens.restype = ctypes.c_int
     lib.marl_grpo_advantages.argtypes = [VP, VP, VP, I32, ctypes.c_float, VP, VP]
+    I64P, I32P = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(I32)
+    lib.marl_balancer_create.argtypes = [ctypes.POINTER(BalancerConfig), I32P, ctypes.POINTER(VP)]
+    lib.marl_balancer_destroy.argtypes = [VP]
+    lib.marl_balancer_destroy.restype = None
+    lib.marl_balancer_submit.argtypes = [VP, I32, I32, I32, I32P]
+    lib.marl_balancer_step.argtypes = [VP, ctypes.POINTER(BalancerStats)]
+    lib.marl_balancer_agent_state.argtypes = [VP, I32, I32P, I64P, I64P]
+    lib.marl_balancer_instance_batch.argtypes = [VP, I32, I32P, I32P, I32P, I32, I32P]
+    lib.marl_balancer_request_state.argtypes = [VP, I32, I32P, I32P, I64P]
     PP = ctypes.POINTER(PrefillShape)
     lib.marl_prefill_workspace_bytes.argtypes = [PP, ctypes.POINTER(SZ)]
     lib.marl_prefill_attn.argtypes = [PP, VP, SZ, VP, VP, VP, VP, VP, VP, ctypes.c_float, VP, VP]
@@ -285,6 +302,57 @@ def prepare_prefill(inp, out_dtype=MARL_OUT_BF16):
 def run_prefill(inp, shape, ws, out):
     return marl_prefill_attn(shape, ws, inp.q, inp.k_pages, inp.v_pages, inp.prefix_block_table, inp.q_start,
                              inp.q_pos0, inp.scale, out)
+
+
+class Balancer:
+    """Handle of the host-side load-balancing simulation (marl_balancer_* in the header)."""
+
+    def __init__(self, instances_per_agent, delta=5, slots_per_instance=1, poll_interval=1, migration_delay=0):
+        self._lib = load_library()
+        cfg = BalancerConfig(len(instances_per_agent), delta, slots_per_instance, poll_interval, migration_delay)
+        arr = (I32 * len(instances_per_agent))(*instances_per_agent)
+        h = VP()
+        _check(self._lib.marl_balancer_create(ctypes.byref(cfg), arr, ctypes.byref(h)), "marl_balancer_create")
+        self._h = h
+        self.num_instances = int(sum(instances_per_agent))
+        self.slots = slots_per_instance
+
+    def close(self):
+        if self._h:
+            self._lib.marl_balancer_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def submit(self, agent: int, request_id: int, gen_len: int) -> int:
+        inst = I32(-1)
+        _check(self._lib.marl_balancer_submit(self._h, agent, request_id, gen_len, ctypes.byref(inst)),
+               "marl_balancer_submit")
+        return int(inst.value)
+
+    def step(self) -> BalancerStats:
+        st = BalancerStats()
+        _check(self._lib.marl_balancer_step(self._h, ctypes.byref(st)), "marl_balancer_step")
+        return st
+
+    def agent_state(self, agent: int):
+        n, w, a = I32(0), ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(self._lib.marl_balancer_agent_state(self._h, agent, ctypes.byref(n), ctypes.byref(w), ctypes.byref(a)),
+               "marl_balancer_agent_state")
+        return int(n.value), int(w.value), int(a.value)
+
+    def instance_batch(self, instance: int):
+        ids, gen = (I32 * self.slots)(), (I32 * self.slots)()
+        owner, n = I32(0), I32(0)
+        _check(self._lib.marl_balancer_instance_batch(self._h, instance, ctypes.byref(owner), ids, gen, self.slots,
+                                                      ctypes.byref(n)), "marl_balancer_instance_batch")
+        return int(owner.value), list(ids[:n.value]), list(gen[:n.value])
+
+    def request_state(self, request_id: int):
+        inst, gen, done = I32(0), I32(0), ctypes.c_int64(0)
+        _check(self._lib.marl_balancer_request_state(self._h, request_id, ctypes.byref(inst), ctypes.byref(gen),
+                                                     ctypes.byref(done)), "marl_balancer_request_state")
+        return int(inst.value), int(gen.value), int(done.value)
 
 
 def marl_profile_begin(max_calls: int):
