@@ -193,6 +193,16 @@ def main():
             tot += ev0.elapsed_time(ev1)
     res["sample_tokens"] = {"us_per_call": tot / 10 * 1e3, "rows": w.num_seqs,
                             "GBps": w.num_seqs * vocab * 2 / (tot / 10 * 1e-3) / 1e9}
+    tot = 0.0
+    for it in range(7):
+        ev0.record()
+        B.marl_sample_tokens_top_p(lp.logits, uniforms, lp.temperature, 0.9, s_tok, s_lp)
+        ev1.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            tot += ev0.elapsed_time(ev1)
+    res["sample_tokens_top_p"] = {"us_per_call": tot / 5 * 1e3, "rows": w.num_seqs, "top_p": 0.9,
+                                  "GBps_of_one_read": w.num_seqs * vocab * 2 / (tot / 5 * 1e-3) / 1e9}
     # prompt (prefill) attention over the workload's prompts: the step that creates the shared
     # prefixes; dense causal MFMA work, reported against the bf16 matrix peak
     del s_ws, uniforms

@@ -216,6 +216,24 @@ int marl_sample_tokens(const void* logits, const float* uniforms, float temperat
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Top-p (nucleus) variant of marl_sample_tokens.  With p = softmax(logits[r, :] / T): rank the
+ * tokens by probability (equal probabilities: lower index first); the nucleus is the shortest
+ * head of that ranking whose total probability is >= top_p; the token is drawn from the
+ * nucleus by inverse CDF in index order,
+ *   token[r] = min { t in nucleus : sum_{v <= t, v in nucleus} p_v > uniforms[r] * p(nucleus) },
+ * and logprob[r] = log p_token (of the untruncated distribution).  top_p in (0, 1]; top_p = 1
+ * keeps every token.  bf16 logits take at most 65536 values, so the kernel finds the nucleus
+ * with an exact count per value instead of a sort; float32 sums decide which value is the
+ * threshold and which token passes u, so within ~1e-6 (relative) of such a boundary the
+ * neighbouring choice may be returned.  A row without a finite logit, or with +inf / NaN,
+ * gives token -1 and NaN.  No workspace.  vocab <= 8388608.  Other arguments as
+ * marl_sample_tokens.
+ */
+int marl_sample_tokens_top_p(const void* logits, const float* uniforms, float temperature,
+                             float top_p, int32_t* out_tokens, float* out_logprobs, int32_t rows,
+                             int32_t vocab, void* stream);
+
+/*
  * Prefill (prompt) attention: the step that creates a prompt's KV prefix, which all samples of
  * that prompt then share (the paper's Parallel Sampling, Section 5.1; the computation itself is
  * textbook causal attention, the paper gives no formula).  Group g brings

@@ -240,6 +240,39 @@ def sample_tokens(logit_bits: np.ndarray, uniforms, temperature: float):
     return tokens, logprobs
 
 
+def nucleus(p: np.ndarray, top_p: float) -> np.ndarray:
+    """Boolean mask of the top-p nucleus: tokens ranked by probability (ties: lower index first),
+    the shortest head of the ranking whose mass is >= top_p; tokens of zero probability are never
+    in it.  If rounding keeps the total below top_p, every token of non-zero probability."""
+    order = np.argsort(-p, kind="stable")            # stable: equal p keep index order
+    csum = np.cumsum(p[order])
+    hit = np.nonzero(csum >= top_p)[0]
+    k = int(hit[0]) + 1 if hit.size else len(p)
+    mask = np.zeros(len(p), dtype=bool)
+    mask[order[:k]] = True
+    return mask & (p > 0)
+
+
+def sample_tokens_top_p(logit_bits: np.ndarray, uniforms, temperature: float, top_p: float):
+    """Inverse-CDF draw inside the nucleus, in index order, with the uniform number scaled to the
+    nucleus mass; log p of the drawn token under the untruncated distribution."""
+    rows = logit_bits.shape[0]
+    tokens = np.full(rows, -1, dtype=np.int64)
+    logprobs = np.full(rows, np.nan)
+    for r in range(rows):
+        p, _ = softmax_cdf(logit_bits[r], temperature)
+        if not np.isfinite(p).all() or not (p > 0).any():
+            continue
+        keep = nucleus(p, top_p)
+        q = np.where(keep, p, 0.0)
+        cdf = np.cumsum(q)
+        hit = np.nonzero(cdf > float(uniforms[r]) * q.sum())[0]
+        t = int(hit[0]) if hit.size else int(np.nonzero(keep)[0][-1])
+        tokens[r] = t
+        logprobs[r] = np.log(p[t])
+    return tokens, logprobs
+
+
 # ------------------------------------------------------------------------------------------
 # GRPO's group-normalised advantage (Shao et al. 2024, the algorithm the paper trains with,
 # Section 8.1): reward minus the group mean, over the group's standard deviation (the root of

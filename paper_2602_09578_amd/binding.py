@@ -92,6 +92,8 @@ def load_library(build_if_missing: bool = True):
     lib.marl_sample_workspace_bytes.argtypes = [I32, I32, ctypes.POINTER(SZ)]
     lib.marl_sample_tokens.argtypes = [VP, VP, ctypes.c_float, VP, VP, I32, I32, VP, SZ, VP]
     lib.marl_sample_workspace_bytes.restype = lib.marl_sample_tokens.restype = ctypes.c_int
+    lib.marl_sample_tokens_top_p.argtypes = [VP, VP, ctypes.c_float, ctypes.c_float, VP, VP, I32, I32, VP]
+    lib.marl_sample_tokens_top_p.restype = ctypes.c_int
     lib.marl_grpo_advantages.argtypes = [VP, VP, VP, I32, ctypes.c_float, VP, VP]
     I64P, I32P = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(I32)
     lib.marl_balancer_create.argtypes = [ctypes.POINTER(BalancerConfig), I32P, ctypes.POINTER(VP)]
@@ -244,6 +246,17 @@ def marl_sample_tokens(logits: torch.Tensor, uniforms: torch.Tensor, temperature
                                            _ptr(out_logprobs), rows, vocab, _ptr(workspace), workspace.numel(),
                                            _stream(logits.device))
     _check(rc, "marl_sample_tokens")
+    return out_tokens, out_logprobs
+
+
+def marl_sample_tokens_top_p(logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, top_p: float,
+                             out_tokens: torch.Tensor, out_logprobs: torch.Tensor):
+    _require_cuda(logits, uniforms, out_tokens, out_logprobs)
+    rows, vocab = logits.shape
+    rc = load_library().marl_sample_tokens_top_p(_ptr(logits), _ptr(uniforms), float(temperature), float(top_p),
+                                                 _ptr(out_tokens), _ptr(out_logprobs), rows, vocab,
+                                                 _stream(logits.device))
+    _check(rc, "marl_sample_tokens_top_p")
     return out_tokens, out_logprobs
 
 

@@ -436,6 +436,29 @@ int marl_sample_tokens(const void* logits, const float* uniforms, float temperat
   return e == hipSuccess ? MARL_OK : hip_fail(e, "sampling kernels");
 }
 
+int marl_sample_tokens_top_p(const void* logits, const float* uniforms, float temperature,
+                             float top_p, int32_t* out_tokens, float* out_logprobs, int32_t rows,
+                             int32_t vocab, void* stream) {
+  if (rows < 0 || vocab < 1) return MARL_INVALID_ARG;
+  if (!isfinite(temperature) || !(temperature > 0.f)) return MARL_INVALID_ARG;
+  if (!(top_p > 0.f) || !(top_p <= 1.f)) return MARL_INVALID_ARG;
+  if (vocab > marl::top_p_max_vocab()) return MARL_UNSUPPORTED;
+  if (rows == 0) return MARL_OK;
+  if (!logits || !uniforms || !out_tokens || !out_logprobs) return MARL_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(logits) % 2 != 0) return MARL_INVALID_ARG;
+  marl::TopPArgs a;
+  a.logits = static_cast<const uint16_t*>(logits);
+  a.uniforms = uniforms;
+  a.out_tokens = out_tokens;
+  a.out_logprobs = out_logprobs;
+  a.rows = rows;
+  a.vocab = vocab;
+  a.inv_temp_log2e = 1.44269504088896340736f / temperature;
+  a.top_p = top_p;
+  const hipError_t e = marl::launch_sample_top_p(a, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "top-p sampling kernel");
+}
+
 // ---- prefill ------------------------------------------------------------------------------------
 namespace {
 int check_prefill_shape(const marl_prefill_shape* s) {

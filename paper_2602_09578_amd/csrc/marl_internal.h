@@ -102,6 +102,17 @@ struct SampleArgs {
 int sample_num_chunks(int vocab);
 hipError_t launch_sample(const SampleArgs& a, hipStream_t st);
 
+struct TopPArgs {
+  const uint16_t* logits;
+  const float* uniforms;
+  int32_t* out_tokens;
+  float* out_logprobs;
+  int32_t rows, vocab;
+  float inv_temp_log2e, top_p;
+};
+int top_p_max_vocab();
+hipError_t launch_sample_top_p(const TopPArgs& a, hipStream_t st);
+
 struct PrefillArgs {
   const uint16_t* q;            // [NT][Hq][128]
   const uint16_t* k_pages;

@@ -185,9 +185,391 @@ __global__ __launch_bounds__(64) void sample_pick_kernel(SampleArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Top-p (nucleus) sampling.  Tokens are ranked by probability (ties: lower index first); the
+// nucleus is the shortest head of that ranking whose probability reaches top_p; the token is
+// drawn from the nucleus by inverse CDF in INDEX order with the caller's uniform number scaled
+// to the nucleus mass.  bf16 logits have at most 65536 distinct values and equal logits have
+// equal probability, so the nucleus is "every token above a threshold value, plus the first c
+// tokens at the threshold value": the kernel finds the threshold with an exact counting
+// histogram over the values instead of sorting 150 k tokens.
+//
+// One workgroup of 1024 threads owns a row and makes these passes over it (the row is re-read
+// from the caches / HBM, 16-byte loads):
+//   1. maximum value and Z = sum 2^(y - M)  (running (max, sum) per thread, fixed-order merge);
+//   2. count histogram in LDS over the 32768 values just below the maximum (order-preserving
+//      16-bit key of the bf16 pattern; integer LDS atomics, so the result does not depend on
+//      the order); a scan of value masses count * 2^(y(value) - M) from the top finds where the
+//      cumulative mass reaches top_p * Z.  If that lies below the window (flat rows with top_p
+//      near 1), the window moves down and the pass repeats (all 65536 values fit 2 windows);
+//   3. per tile of 8192 tokens the nucleus mass and the number of threshold-value tokens; a
+//      sequential walk over the tile sums finds the tile in which the scaled uniform is
+//      passed, a workgroup scan inside that tile finds the token.
+// ---------------------------------------------------------------------------------------
+constexpr int kTpThreads = 1024;
+constexpr int kTpWaves = kTpThreads / 64;
+constexpr int kWin = 32768;                  // histogram window, in values (keys)
+constexpr int kTile = kTpThreads * 8;        // tokens per tile of pass 3
+constexpr int kLowestKey = 0x0080;           // key of the most negative finite bf16; below: -inf, NaN
+constexpr int kHighestKey = 0xff7f;          // key of the largest finite bf16; above: +inf, NaN
+
+__device__ __forceinline__ int key_of(uint32_t bits) {   // larger value <=> larger key; -0 counts as +0
+  if ((bits & 0x7fffu) == 0) bits = 0;
+  return (bits & 0x8000u) ? (int)(~bits & 0xffffu) : (int)(bits | 0x8000u);
+}
+__device__ __forceinline__ float value_of_key(int key) {
+  const uint32_t bits = (key & 0x8000) ? (uint32_t)(key & 0x7fff) : (~(uint32_t)key & 0xffffu);
+  return __uint_as_float(bits << 16);
+}
+
+// the 8 logits at x[pos .. pos+8) as four packed words; positions past the end read as -inf
+__device__ __forceinline__ u32x4 load8_words(const uint16_t* x, long pos, long end) {
+  const uint16_t* p = x + pos;
+  if (pos + 8 <= end && (reinterpret_cast<uintptr_t>(p) & 15) == 0) return *reinterpret_cast<const u32x4*>(p);
+  u32x4 v;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t lo = pos + 2 * d < end ? p[2 * d] : 0xff80u;
+    const uint32_t hi = pos + 2 * d + 1 < end ? p[2 * d + 1] : 0xff80u;
+    v[d] = lo | (hi << 16);
+  }
+  return v;
+}
+
+struct TpShared {
+  uint32_t hist[kWin];          // pass 2: counts; pass 3: per-(tile, wave) sums (reused)
+  double wave_d[kTpWaves];
+  float wave_f[kTpWaves];
+  float wave_m[kTpWaves];
+  int wave_i[kTpWaves];
+  int found_at;                 // smallest scan position / thread index that meets a condition
+  int thr_key, thr_cnt;         // threshold value (key) and how many tokens have it
+  double thr_above;             // mass strictly above the threshold value
+  int tile, ties_before;
+  float cum_before;
+  int out_tok;
+  float out_y;
+};
+
+// exclusive scans over the workgroup in thread order (fixed order: bit-identical reruns)
+__device__ __forceinline__ double block_excl_scan_d(double v, double& total, TpShared& sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) sh.wave_d[wave] = inc;
+  __syncthreads();
+  double before = 0.0, all = 0.0;
+#pragma unroll
+  for (int w = 0; w < kTpWaves; ++w) {
+    if (w < wave) before += sh.wave_d[w];
+    all += sh.wave_d[w];
+  }
+  total = all;
+  return before + inc - v;
+}
+__device__ __forceinline__ float block_excl_scan_f(float v, TpShared& sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inc = wave_inclusive_scan(v, lane);
+  __syncthreads();
+  if (lane == 63) sh.wave_f[wave] = inc;
+  __syncthreads();
+  float before = 0.f;
+#pragma unroll
+  for (int w = 0; w < kTpWaves; ++w)
+    if (w < wave) before += sh.wave_f[w];
+  return before + inc - v;
+}
+__device__ __forceinline__ int block_excl_scan_i(int v, TpShared& sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) sh.wave_i[wave] = inc;
+  __syncthreads();
+  int before = 0;
+#pragma unroll
+  for (int w = 0; w < kTpWaves; ++w)
+    if (w < wave) before += sh.wave_i[w];
+  return before + inc - v;
+}
+
+// One sweep over a row: calls fn(tile, the four 32-bit words that hold this thread's 8 tokens
+// of the tile, token 2d in the low half of word d) for every tile in order; positions past the
+// end of the row read as -inf.  Full tiles of a 16-byte aligned row are fetched four at a time
+// (64 bytes per thread in flight) before any of them is used.
+template <class F>
+__device__ __forceinline__ void sweep_row(const uint16_t* x, long V, int tid, F&& fn) {
+  const int ntiles = (int)((V + kTile - 1) / kTile);
+  const int nfull = (reinterpret_cast<uintptr_t>(x) & 15) == 0 ? (int)(V / kTile) : 0;
+  int t = 0;
+  for (; t + 4 <= nfull; t += 4) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      v[u] = *reinterpret_cast<const u32x4*>(x + (long)(t + u) * kTile + (long)tid * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) fn(t + u, v[u]);
+  }
+  for (; t < ntiles; ++t) fn(t, load8_words(x, (long)t * kTile + (long)tid * 8, V));
+}
+// the two bf16 of a word widened to float
+__device__ __forceinline__ float lo_val(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_val(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
+  __shared__ TpShared sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.x;
+  const uint16_t* x = a.logits + (size_t)row * a.vocab;
+  const float c = a.inv_temp_log2e;
+  const long V = a.vocab;
+  const int ntiles = (int)((V + kTile - 1) / kTile);
+
+  // ---- pass 1: largest value and Z relative to it, in one sweep -------------------------------
+  // per thread a running (largest y so far, sum relative to it); merged in thread order
+  float xrun = -INFINITY, mrun = -INFINITY, zrun = 0.f;   // largest raw logit, the same times c, sum
+  sweep_row(x, V, tid, [&](int, u32x4 v) {
+    float r[8];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) { r[2 * d] = lo_val(v[d]); r[2 * d + 1] = hi_val(v[d]); }
+    const float x8 = fmaxf(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])), fmaxf(fmaxf(r[4], r[5]), fmaxf(r[6], r[7])));
+    if (x8 > xrun) {                       // c > 0: the largest raw logit is the largest scaled one
+      const float m8 = x8 * c;
+      zrun *= ex2(mrun - m8);              // mrun = -inf: zrun is 0 and stays 0
+      xrun = x8;
+      mrun = m8;
+    }
+    if (xrun > -INFINITY) {
+      float s8 = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s8 += ex2(__builtin_fmaf(r[e], c, -mrun));
+      zrun += s8;
+    }
+  });
+  float xmax = xrun;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) xmax = fmaxf(xmax, __shfl_xor(xmax, d));
+  if (lane == 0) sh.wave_m[wave] = xmax;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kTpWaves; ++w) xmax = fmaxf(xmax, sh.wave_m[w]);
+  const float M = xmax * c;
+  double ztot;
+  block_excl_scan_d(xrun > -INFINITY ? (double)zrun * (double)ex2(mrun - M) : 0.0, ztot, sh);
+  const double Z = ztot;
+  if (!(xmax > -INFINITY) || !(Z > 0.0) || !(Z < 1e300)) {   // no finite logit, or +inf / NaN: nothing to draw
+    if (tid == 0) {
+      a.out_tokens[row] = -1;
+      a.out_logprobs[row] = __uint_as_float(0x7fc00000u);
+    }
+    return;
+  }
+  const int kmax = key_of(__float_as_uint(xmax) >> 16);
+  // the weight of a value, computed the same way everywhere: 2^(fma(value, c, -M))
+  auto weight = [&](int key) { return key >= kLowestKey ? ex2(__builtin_fmaf(value_of_key(key), c, -M)) : 0.f; };
+
+  // ---- pass 2: the threshold value --------------------------------------------------------
+  // thr_key = -1: every token with a finite logit is in the nucleus
+  if (tid == 0) { sh.thr_key = -1; sh.thr_cnt = 0; sh.thr_above = 0.0; }
+  if (a.top_p < 1.f) {
+    const double tau = (double)a.top_p * Z;
+    double above = 0.0;                       // mass of the values above the window
+    for (int hi = kmax; hi >= kLowestKey; hi -= kWin) {
+      const int lo = hi - (kWin - 1);
+      for (int i = tid; i < kWin; i += kTpThreads) sh.hist[i] = 0;
+      if (tid == 0) sh.found_at = kWin;
+      __syncthreads();
+      const int lo_eff = max(lo, kLowestKey);
+      const unsigned span = (unsigned)(hi - lo_eff);
+      sweep_row(x, V, tid, [&](int, u32x4 v) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const int k0 = key_of(v[d] & 0xffffu), k1 = key_of(v[d] >> 16);
+          if ((unsigned)(k0 - lo_eff) <= span) atomicAdd(&sh.hist[k0 - lo], 1u);
+          if ((unsigned)(k1 - lo_eff) <= span) atomicAdd(&sh.hist[k1 - lo], 1u);
+        }
+      });
+      __syncthreads();
+      // position j of the scan is the value hi - j; thread t owns j = 32 t .. 32 t + 31
+      constexpr int kPer = kWin / kTpThreads;
+      auto mass_at = [&](int q) {
+        const int key = hi - (tid * kPer + q);
+        const uint32_t cnt = sh.hist[key - lo];
+        return cnt ? (double)cnt * (double)weight(key) : 0.0;
+      };
+      double mine = 0.0;
+#pragma unroll 4
+      for (int q = 0; q < kPer; ++q) mine += mass_at(q);
+      double window_total;
+      const double before = above + block_excl_scan_d(mine, window_total, sh);
+      // first scan position at which the cumulative mass reaches tau: every thread at or past
+      // the crossing proposes its first such position, the smallest wins (robust against the
+      // last-bit differences between neighbouring threads' scan values)
+      int my_pos = kWin;
+      double my_above = 0.0;
+      if (before + mine >= tau) {
+        double run = before;
+#pragma unroll 1
+        for (int q = 0; q < kPer; ++q) {
+          const double m = mass_at(q);
+          if (m > 0.0 && run + m >= tau) { my_pos = tid * kPer + q; my_above = run; break; }
+          run += m;
+        }
+        if (my_pos < kWin) atomicMin(&sh.found_at, my_pos);
+      }
+      __syncthreads();
+      if (my_pos < kWin && my_pos == sh.found_at) {
+        const int key = hi - my_pos;
+        sh.thr_key = key;
+        sh.thr_cnt = (int)sh.hist[key - lo];
+        sh.thr_above = my_above;
+      }
+      __syncthreads();
+      if (sh.found_at < kWin) break;          // workgroup-uniform
+      above += window_total;
+    }
+  }
+  __syncthreads();
+  const int thr_key = sh.thr_key;
+  // how many of the threshold-value tokens (in index order) the nucleus takes
+  int ties_kept = 0;
+  float thr_w = 0.f;
+  double nucleus = Z;
+  if (thr_key >= 0) {
+    thr_w = weight(thr_key);
+    const double need = ((double)a.top_p * Z - sh.thr_above) / (double)thr_w;
+    ties_kept = (int)fmin(fmax(ceil(need), 1.0), (double)sh.thr_cnt);
+    nucleus = sh.thr_above + (double)ties_kept * (double)thr_w;
+  }
+  const float target = (float)((double)a.uniforms[row] * nucleus);
+  // pass 3 compares raw logit values (every bf16 is exact in float; -0 == +0 as in the keys);
+  // with no threshold every finite logit is above it
+  const float thr_x = thr_key >= 0 ? value_of_key(thr_key) : -INFINITY;
+
+  // ---- pass 3: inverse CDF over the nucleus in index order ----------------------------------
+  // per tile and wave: mass of the tokens above the threshold, number of tokens at it
+  float* part_m = reinterpret_cast<float*>(sh.hist);             // [ntiles][kTpWaves]
+  int* part_n = reinterpret_cast<int*>(sh.hist) + kWin / 2;      // [ntiles][kTpWaves]
+  __syncthreads();                                               // the histogram is no longer read
+  sweep_row(x, V, tid, [&](int t, u32x4 v) {
+    float m8 = 0.f;
+    int n8 = 0;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const float r0 = lo_val(v[d]), r1 = hi_val(v[d]);
+      const float w0 = ex2(__builtin_fmaf(r0, c, -M)), w1 = ex2(__builtin_fmaf(r1, c, -M));
+      m8 += r0 > thr_x ? w0 : 0.f;
+      m8 += r1 > thr_x ? w1 : 0.f;
+      n8 += (r0 == thr_x) + (r1 == thr_x);
+    }
+    m8 = wave_sum(m8);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) n8 += __shfl_xor(n8, d);
+    if (lane == 0) { part_m[t * kTpWaves + wave] = m8; part_n[t * kTpWaves + wave] = n8; }
+  });
+  __syncthreads();
+  if (tid == 0) {
+    float cum = 0.f;
+    int ties = 0, tile = -1, last_tile = 0, last_ties = 0;
+    float last_cum = 0.f;
+    for (int t = 0; t < ntiles && tile < 0; ++t) {
+      float m = 0.f;
+      int n = 0;
+      for (int w = 0; w < kTpWaves; ++w) { m += part_m[t * kTpWaves + w]; n += part_n[t * kTpWaves + w]; }
+      const float kept = m + thr_w * (float)min(n, max(0, ties_kept - ties));
+      if (kept > 0.f) { last_tile = t; last_cum = cum; last_ties = ties; }
+      if (cum + kept > target) { tile = t; break; }
+      cum += kept;
+      ties += n;
+    }
+    if (tile < 0) {               // rounding left the target at or above the total: the last token
+      tile = last_tile;           // of the nucleus is taken (inside the tile, below)
+      cum = last_cum;
+      ties = last_ties;
+    }
+    sh.tile = tile;
+    sh.cum_before = cum;
+    sh.ties_before = ties;
+    sh.found_at = kTpThreads;
+    sh.out_tok = -1;
+  }
+  __syncthreads();
+  {
+    const int t = sh.tile;
+    const long pos = (long)t * kTile + (long)tid * 8;
+    const u32x4 v = load8_words(x, pos, V);
+    float r[8];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) { r[2 * d] = lo_val(v[d]); r[2 * d + 1] = hi_val(v[d]); }
+    int n8 = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) n8 += r[e] == thr_x;
+    int rank = sh.ties_before + block_excl_scan_i(n8, sh);       // threshold-value tokens before this thread
+    float w8[8], m8 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float w = 0.f;
+      if (r[e] > thr_x) w = ex2(__builtin_fmaf(r[e], c, -M));
+      else if (r[e] == thr_x) { if (rank < ties_kept) w = thr_w; ++rank; }
+      w8[e] = w;
+      m8 += w;
+    }
+    const float before = sh.cum_before + block_excl_scan_f(m8, sh);
+    const bool pass = before + m8 > target && m8 > 0.f;
+    if (pass) atomicMin(&sh.found_at, tid);
+    // the last thread of the tile that holds a nucleus token, for the rounding fallback
+    if (m8 > 0.f) atomicMax(&sh.out_tok, tid);
+    __syncthreads();
+    const int winner = sh.found_at < kTpThreads ? sh.found_at : sh.out_tok;
+    const bool fallback = sh.found_at >= kTpThreads;
+    if (winner < 0 && tid == 0) {   // no nucleus token in the tile: cannot happen for Z > 0
+      a.out_tokens[row] = -1;
+      a.out_logprobs[row] = __uint_as_float(0x7fc00000u);
+    }
+    if (tid == winner) {
+      float run = before;
+      int e_pick = -1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (w8[e] > 0.f) {
+          run += w8[e];
+          if (fallback) e_pick = e;                               // last nucleus token of the thread
+          else if (e_pick < 0 && run > target) e_pick = e;
+        }
+      }
+      if (e_pick < 0) {                                           // cannot happen: pass implies a hit
+#pragma unroll
+        for (int e = 0; e < 8; ++e) if (w8[e] > 0.f) e_pick = e;
+      }
+      float r_pick = r[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) if (e == e_pick) r_pick = r[e];
+      a.out_tokens[row] = (int)(pos + e_pick);
+      a.out_logprobs[row] = (__builtin_fmaf(r_pick, c, -M) - __builtin_amdgcn_logf((float)Z)) * 0.69314718055994530942f;
+    }
+  }
+}
+
 }  // namespace
 
 int sample_num_chunks(int vocab) { return (vocab + kChunk - 1) / kChunk; }
+
+int top_p_max_vocab() { return (kWin / 2 / kTpWaves) * kTile; }   // tile sums must fit the LDS buffer
+
+hipError_t launch_sample_top_p(const TopPArgs& a, hipStream_t st) {
+  if (a.rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(sample_top_p_kernel, dim3((unsigned)a.rows), dim3(kTpThreads), 0, st, a);
+  return hipGetLastError();
+}
 
 hipError_t launch_sample(const SampleArgs& a, hipStream_t st) {
   if (a.rows == 0) return hipSuccess;
