@@ -29,18 +29,20 @@ HBM_PEAK_GBPS = 8000.0
 # (profiles/decode_step_qwen7b_hbm_counters.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors a copy kernel of known size gives).  Valid only for the kernel source it was taken
 # with: reported as null when the source has changed since.
-SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5525.9e6 + 29.0e6,
-                  "attn_kernels_sha256": "ec494d28fe956530bed81cbca982aa7e8c315c42e0db420c0742edc85fa28e96"}
+SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5527.0e6 + 29.0e6,
+                  "kernel_sources_sha256": "8d4958473408b1810e339e3104bb8242042eee7aaf8d74408005a7d41dc640ed"}
+SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 
 def suffix_traffic(workload: str):
     import hashlib
-    src = os.path.join(ROOT, "paper_2602_09578_amd", "csrc", "attn_kernels.hip")
+    h = hashlib.sha256()
     try:
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        for name in SUFFIX_SOURCES:
+            h.update(open(os.path.join(ROOT, "paper_2602_09578_amd", "csrc", name), "rb").read())
     except OSError:
         return None
-    if workload != SUFFIX_TRAFFIC["workload"] or digest != SUFFIX_TRAFFIC["attn_kernels_sha256"]:
+    if workload != SUFFIX_TRAFFIC["workload"] or h.hexdigest() != SUFFIX_TRAFFIC["kernel_sources_sha256"]:
         return None
     return SUFFIX_TRAFFIC["bytes"]
 
