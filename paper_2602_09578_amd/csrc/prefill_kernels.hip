@@ -8,13 +8,17 @@
 // positions are then context that is already in the cache (chunked prefill).
 //
 // Structure.  Query rows of a (group, KV head) are flattened as rho = token * R + head-in-group
-// and cut into blocks of kQB rows; one work item = (group, row block, KV head).  The item
-// streams keys/values 0 .. (last position of the block) through a triple-buffered LDS tile,
-// 32 tokens (two pages) per step, exactly as the decode prefix kernel does; the waves split the
-// block's 16-row tiles.  Causality costs little: a block spans kQB / R consecutive tokens, so
-// only its last one or two steps need the per-row mask, and a tile skips steps that lie
-// entirely beyond its rows.  A block sees all of its keys, so the output is normalised and
-// written directly (no partials, no merge).
+// and cut into equal blocks of at most kQB = 192 rows; one work item = (group, row block, KV
+// head).  The item streams keys/values 0 .. (last position of the block) through a ring of four
+// LDS step buffers, 32 tokens (two pages, 16 KB) per step, in the XOR-swizzled layout of the
+// decode prefix kernel; the four waves split the block's 16-row tiles (up to three each).  The
+// steps go from global memory straight into LDS (global_load_lds_dwordx4, no staging
+// registers), which is what leaves room for the third tile: the kernel is bound by the LDS
+// operand reads (every wave reads the whole step for its rows), so more rows per wave is what
+// makes it faster.  Causality costs little: a block spans kQB / R consecutive tokens, so only
+// its last one or two steps need the per-row mask, and a tile skips steps that lie entirely
+// beyond its rows.  A block sees all of its keys, so the output is normalised and written
+// directly (no partials, no merge).
 //
 // Work distribution: a one-workgroup plan kernel turns q_start into the running number of
 // row blocks per group and lists the blocks (group, first row), inside a group last-first
@@ -26,7 +30,7 @@ namespace marl {
 namespace {
 
 #ifndef MARL_PREFILL_MT
-#define MARL_PREFILL_MT 2
+#define MARL_PREFILL_MT 3
 #endif
 #ifndef MARL_PREFILL_NW
 #define MARL_PREFILL_NW 4
@@ -36,14 +40,22 @@ namespace {
 #endif
 constexpr int kMT = MARL_PREFILL_MT;          // 16-row tiles per wave
 constexpr int kNW = MARL_PREFILL_NW;          // waves per workgroup
-constexpr int kQB = 16 * kMT * kNW;           // query rows per work item
+constexpr int kQB = 16 * kMT * kNW;           // most query rows of one work item
 constexpr int kPfThreads = 64 * kNW;
 constexpr int kPfStepBytes = 2 * kBlockTok * kD * 2;   // K + V of one 32-token step
 constexpr int kPlanThreadsPf = 1024;
 
+#ifndef MARL_PREFILL_DIRECT
+#define MARL_PREFILL_DIRECT 1
+#endif
+// LDS step buffers: 3 with register staging; 4 with direct global-to-LDS loads (two workgroups
+// of 64 KB per CU)
+constexpr int kPfStages = MARL_PREFILL_DIRECT ? 4 : 3;
 struct PrefillLds {
-  __attribute__((aligned(16))) char buf[3][kPfStepBytes];
+  __attribute__((aligned(16))) char buf[kPfStages][kPfStepBytes];
 };
+// s_waitcnt immediate that waits only for the vector-memory counter to drop to n (gfx9 encoding)
+constexpr int pf_vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (7 << 4) | (0xf << 8); }
 
 // counters at the head of the workspace (same slots as the decode plan uses, so that
 // marl_attn_read_flags reads this workspace too); block_start[NG + 1] follows the header
@@ -59,6 +71,15 @@ __device__ __forceinline__ int group_tokens(const PrefillArgs& a, int g, int& fl
   return n;
 }
 
+// A group's nrows query rows are cut into ceil(nrows / kQB) blocks of equal size (a multiple of
+// 16 rows), not into full blocks and a remainder: 224 rows are two blocks of 112 (7 tiles each
+// over the waves), not 192 + 32.
+__device__ __forceinline__ int blocks_of(long nrows) { return (int)((nrows + kQB - 1) / kQB); }
+__device__ __forceinline__ int block_rows(long nrows) {
+  const long nb = (nrows + kQB - 1) / kQB;
+  return nb ? (int)(((nrows + nb - 1) / nb + 15) / 16 * 16) : 0;
+}
+
 __global__ __launch_bounds__(kPlanThreadsPf) void prefill_plan_kernel(PrefillArgs a) {
   __shared__ long long part[kPlanThreadsPf];   // 64-bit: inconsistent inputs must not wrap the sums
   __shared__ long long carry;
@@ -70,7 +91,11 @@ __global__ __launch_bounds__(kPlanThreadsPf) void prefill_plan_kernel(PrefillArg
   for (int g0 = 0; g0 < a.NG; g0 += kPlanThreadsPf) {
     const int g = g0 + tid;
     int nb = 0;
-    if (g < a.NG) nb = (int)(((long)group_tokens(a, g, flag) * a.R + kQB - 1) / kQB);
+    long nrows = 0;
+    if (g < a.NG) {
+      nrows = (long)group_tokens(a, g, flag) * a.R;
+      nb = blocks_of(nrows);
+    }
     // groups that overlap in q could ask for more blocks than the workspace was sized for
     // (its bound assumes they share no rows): such a group is dropped
     if (nb > a.max_blocks) { nb = 0; flag |= MARL_FLAG_BAD_GROUP; }
@@ -94,7 +119,8 @@ __global__ __launch_bounds__(kPlanThreadsPf) void prefill_plan_kernel(PrefillArg
       }
       a.block_start[g] = first;
       // the group's work items, last row block (most keys) first
-      for (int k = 0; k < nb; ++k) a.items[first + k] = make_int2(g, (nb - 1 - k) * kQB);
+      const int qb = block_rows(nrows);
+      for (int k = 0; k < nb; ++k) a.items[first + k] = make_int2(g, (nb - 1 - k) * qb);
     }
     __syncthreads();
     if (tid == kPlanThreadsPf - 1) carry += part[tid];
@@ -124,7 +150,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   const int32_t* table_row = a.prefix_table + (size_t)g * a.max_pp;
   const float sc = fmaxf(fabsf(a.scale) * 1.44269504088896340736f, 1e-30f);
   const uint32_t sign_flip = a.scale < 0.f ? 0x80008000u : 0u;
-  const int rows_here = min(kQB, nrows - row_begin);
+  const int rows_here = min(block_rows(nrows), nrows - row_begin);
   // keys this block needs: 0 .. position of its last row
   const int tok_end = pos0 + (row_begin + rows_here - 1) / a.R + 1;
 
@@ -187,6 +213,38 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   // rows of 256 B with the 16-byte chunk index XOR-ed with a key of the row, V as
   // [page][channel][2 halves of 8 slots] with the unit index XOR-ed with (unit >> 3) & 1, so
   // that the 8 lanes of one operand read hit 8 different bank groups.
+#if MARL_PREFILL_DIRECT
+  // Direct variant: global_load_lds_dwordx4 moves the vectors from global memory straight into
+  // LDS (the 64 lanes of a wave fill 1 KB in lane order, no registers in between).  Wave `wave`
+  // fills, for k < kLoads, the 64 slots from slot w0 of region k * kNW/4 + wave/4; the XOR
+  // swizzle (an involution inside a key row / a pair of value units) is applied on the source
+  // side: the lane that fills slot s fetches vector swz(s).
+  static_assert(kNW % 4 == 0, "a wave's 64 vectors must lie in one 256-vector region");
+  const int w0 = (wave & 3) * 64;
+  uint32_t src_off[kLoads];
+  int region[kLoads];
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    region[k] = k * (kNW / 4) + (wave >> 2);
+    const int s_pos = w0 + lane;
+    const int slot = s_pos >> 4;
+    const int src = (region[k] >> 1) ? (s_pos ^ ((s_pos >> 3) & 1))
+                                     : ((slot << 4) | ((s_pos & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)));
+    src_off[k] = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)src * 16;
+  }
+  auto issue = [&](int p0, int p1, char* buf) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const char* base = reinterpret_cast<const char*>((region[k] >> 1) ? a.v_pages : a.k_pages) +
+                         (size_t)((region[k] & 1) ? p1 : p0) * page_bytes;
+      char* dst = buf + region[k] * 4096 + w0 * 16;   // wave-uniform; lane l lands at dst + 16 l
+      __builtin_amdgcn_global_load_lds(
+          reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(base + src_off[k])),
+          reinterpret_cast<__attribute__((address_space(3))) void*>((uint32_t)reinterpret_cast<uintptr_t>(dst)),
+          16, 0, 0);
+    }
+  };
+#else
   static_assert(kNW % 4 == 0, "a wave's 64 vectors must lie in one 256-vector region");
   const int w = tid & 255;
   const uint32_t lane_off = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)w * 16;
@@ -211,6 +269,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) *reinterpret_cast<u32x4*>(buf + lds_off[k]) = st[k];
   };
+#endif
   const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
   const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
 
@@ -287,6 +346,30 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
       }
   };
 
+#if MARL_PREFILL_DIRECT
+  // ring of kPfStages LDS buffers: per iteration wait until this wave's part of step n has landed
+  // (all but the youngest kPfStages-2 steps' loads), a bare workgroup barrier (everybody's part
+  // has landed and everybody has finished reading buffer (n-1) % kPfStages; a fence would wait
+  // for every outstanding load), then the loads of step n+kPfStages-1 go into that buffer
+  int p0, p1;
+#pragma unroll
+  for (int s0 = 0; s0 < kPfStages - 1; ++s0) {
+    load_ids(s0, p0, p1);
+    issue(p0, p1, lds.buf[s0]);
+  }
+  load_ids(kPfStages - 1, p0, p1);
+  for (int n = 0; n < nsteps; ++n) {
+    __builtin_amdgcn_s_waitcnt(pf_vmcnt_imm((kPfStages - 2) * kLoads));
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(p0, p1, lds.buf[(n + kPfStages - 1) % kPfStages]);
+    load_ids(n + kPfStages, p0, p1);
+    compute(n, lds.buf[n % kPfStages]);
+  }
+  __builtin_amdgcn_s_waitcnt(pf_vmcnt_imm(0));
+  __syncthreads();
+#else
   // three register stages and three LDS buffers, as in the decode prefix kernel
   u32x4 st0[kLoads], st1[kLoads], st2[kLoads];
   int p0, p1;
@@ -321,6 +404,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
     }
   }
 
+#endif
   // lane (i, j) holds channels 16*ct + 4*j .. +3 of q-row i
 #pragma unroll
   for (int qt = 0; qt < kMT; ++qt) {
