@@ -153,3 +153,55 @@ def test_argument_errors():
     assert lib.marl_balancer_instance_batch(h, 9, None, None, None, 0, ctypes.byref(n)) == -1
     assert lib.marl_balancer_request_state(h, 7, None, None, None) == -1
     lib.marl_balancer_destroy(h)
+
+
+def test_balancer_host_code_runs_clean_under_asan_ubsan(tmp_path):
+    """The balancer is host C++: built alone with g++ and the sanitizers, a seeded trace with
+    migrations runs clean and matches the reference."""
+    import os, subprocess, sys, textwrap
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib = tmp_path / "libbalancer_san.so"
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-fPIC", "-shared", "-x", "c++",
+                           "-I" + os.path.join(root, "include"), "-o", str(lib),
+                           os.path.join(root, "paper_2602_09578_amd", "csrc", "balancer.hip")])
+    script = textwrap.dedent(f"""
+        import ctypes, sys
+        import numpy as np
+        sys.path.insert(0, {root!r})
+        from oracle.balancer_ref import BalancerRef
+        lib = ctypes.CDLL({str(lib)!r})
+        I32, I64, VP = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        lib.marl_balancer_submit.argtypes = [VP, I32, I32, I32, ctypes.POINTER(I32)]
+        lib.marl_balancer_step.argtypes = [VP, VP]
+        lib.marl_balancer_request_state.argtypes = [VP, I32, ctypes.POINTER(I32), ctypes.POINTER(I32), ctypes.POINTER(I64)]
+        lib.marl_balancer_destroy.argtypes = [VP]
+        lib.marl_balancer_destroy.restype = None
+        per_agent = [3, 1, 2, 4]
+        cfg = (I32 * 5)(4, 2, 2, 3, 4)          # agents, delta, slots, poll interval, migration delay
+        h = VP()
+        assert lib.marl_balancer_create(cfg, (I32 * 4)(*per_agent), ctypes.byref(h)) == 0
+        ref = BalancerRef(per_agent, 2, 2, 3, 4)
+        rng = np.random.default_rng(3)
+        rid = 0
+        for t in range(200):
+            for a, rate in enumerate((1.2, 0.05, 0.1, 0.05)):
+                for _ in range(rng.poisson(rate) if t < 120 else 0):
+                    n = int(rng.integers(1, 30)); inst = I32(-1)
+                    assert lib.marl_balancer_submit(h, a, rid, n, ctypes.byref(inst)) == 0
+                    assert inst.value == ref.submit(a, rid, n)
+                    rid += 1
+            assert lib.marl_balancer_step(h, None) == 0
+            ref.step()
+        assert ref.migrations > 0
+        for r in ref.reqs.values():
+            i, g, d = I32(0), I32(0), I64(0)
+            assert lib.marl_balancer_request_state(h, r.id, ctypes.byref(i), ctypes.byref(g), ctypes.byref(d)) == 0
+            assert (i.value, g.value, d.value) == (r.instance, r.generated, r.done_step)
+        lib.marl_balancer_destroy(h)
+        print("clean")
+    """)
+    asan = subprocess.check_output(["g++", "-print-file-name=libasan.so"], text=True).strip()
+    env = dict(os.environ, LD_PRELOAD=(os.environ.get("LD_PRELOAD", "") + " " + asan).strip(), ASAN_OPTIONS="detect_leaks=0")   # the interpreter itself leaks at exit
+    r = subprocess.run([sys.executable, "-c", script], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0 and "clean" in r.stdout, r.stdout[-3000:]
