@@ -196,16 +196,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
 // live in LDS, and global memory only sees the final stores.  The general kernel above pays
 // a chain of ~30 dependent global round trips; this one pays one.
 // ---------------------------------------------------------------------------------------
-constexpr int kSmallMaxSeqs = 8192;
-constexpr int kSmallMaxGroups = 2048;
+// Two sizes: up to 8192 sequences in 2048 groups (56 KB of LDS), and up to 32768 sequences in
+// 8192 groups with 16-bit member ids (130 KB of the 160 KB).
 constexpr int kSmallMaxClasses = 256;
-constexpr int kSeqsPerThread = kSmallMaxSeqs / kPlanThreads;
-constexpr int kGroupsPerThread = kSmallMaxGroups / kPlanThreads;
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
+template <int kSmallMaxSeqs, int kSmallMaxGroups, class MemberId>
+__device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
+  constexpr int kSeqsPerThread = kSmallMaxSeqs / kPlanThreads;
+  constexpr int kGroupsPerThread = kSmallMaxGroups / kPlanThreads;
   __shared__ int cnt[kSmallMaxGroups];
   __shared__ int start[kSmallMaxGroups + 1];
-  __shared__ int members[kSmallMaxSeqs];
+  __shared__ MemberId members[kSmallMaxSeqs];
   __shared__ int hist_s[kSmallMaxClasses];
   __shared__ int hist_p[kSmallMaxClasses];
   __shared__ int tmp[17];
@@ -216,14 +217,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
   const int max_st = a.max_sp * kPage, max_pt = a.max_pp * kPage;
   int flags = 0;
 
-  // inputs -> registers (the only loads from global memory)
-  int g_of[kSeqsPerThread], S_of[kSeqsPerThread], rank_of[kSeqsPerThread];
+  // inputs -> registers (the only loads from global memory).  The larger size has no room for
+  // 3 x 32 values per thread: it keeps only the ranks and re-reads group ids and lengths (cache
+  // hits) in the later phases.
+  constexpr bool kKeep = kSeqsPerThread <= 8;
+  int g_keep[kKeep ? kSeqsPerThread : 1], S_keep[kKeep ? kSeqsPerThread : 1], rank_of[kSeqsPerThread];
+  if constexpr (kKeep) {
 #pragma unroll
-  for (int k = 0; k < kSeqsPerThread; ++k) {
-    const int s = tid + k * kPlanThreads;
-    g_of[k] = s < a.NS ? a.group_of_seq[s] : -1;
-    S_of[k] = s < a.NS ? a.suffix_lens[s] : 0;
+    for (int k = 0; k < kSeqsPerThread; ++k) {
+      const int s = tid + k * kPlanThreads;
+      g_keep[k] = s < a.NS ? a.group_of_seq[s] : -1;
+      S_keep[k] = s < a.NS ? a.suffix_lens[s] : 0;
+    }
   }
+  int ignored = 0;
+  auto G = [&](int k) {   // group id of this thread's k-th sequence (only called for s < NS)
+    if constexpr (kKeep) return g_keep[k]; else return a.group_of_seq[tid + k * kPlanThreads];
+  };
+  auto S_len = [&](int k) {   // its clamped suffix length
+    if constexpr (kKeep) return S_keep[k]; else return clamp_len(a.suffix_lens[tid + k * kPlanThreads], max_st, ignored);
+  };
   int P_of[kGroupsPerThread];
 #pragma unroll
   for (int k = 0; k < kGroupsPerThread; ++k) {
@@ -241,10 +254,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
     const int s = tid + k * kPlanThreads;
     rank_of[k] = -1;
     if (s < a.NS) {
-      if ((unsigned)g_of[k] < (unsigned)a.NG) rank_of[k] = atomicAdd(&cnt[g_of[k]], 1);
+      const int g = G(k);
+      if ((unsigned)g < (unsigned)a.NG) rank_of[k] = atomicAdd(&cnt[g], 1);
       else flags |= MARL_FLAG_BAD_GROUP;
-      S_of[k] = clamp_len(S_of[k], max_st, flags);
-      const int nfull = S_of[k] / Cs, tail = S_of[k] % Cs;
+      int S;
+      if constexpr (kKeep) S = S_keep[k] = clamp_len(S_keep[k], max_st, flags);
+      else S = clamp_len(a.suffix_lens[s], max_st, flags);
+      const int nfull = S / Cs, tail = S % Cs;
       if (nfull) atomicAdd(&hist_s[0], nfull);
       if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
       const int nlong = (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
@@ -276,10 +292,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
   for (int k = 0; k < kSeqsPerThread; ++k) {
     const int s = tid + k * kPlanThreads;
     if (s < a.NS) {
-      if (rank_of[k] >= 0) members[start[g_of[k]] + rank_of[k]] = s;
-      const int S = S_of[k];
+      const int g = G(k);
+      if (rank_of[k] >= 0) members[start[g] + rank_of[k]] = (MemberId)s;
+      const int S = S_len(k);
       int dummy = 0;
-      const int P = rank_of[k] >= 0 ? clamp_len(a.prefix_lens[g_of[k]], max_pt, dummy) : 0;
+      const int P = rank_of[k] >= 0 ? clamp_len(a.prefix_lens[g], max_pt, dummy) : 0;
       a.seq_chunks[s] = ((P + Cp - 1) / Cp) | (((S + Cs - 1) / Cs) << 16);
       const int nfull = S / Cs, tail = S % Cs;
       if (nfull) {
@@ -324,11 +341,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
   for (int k = 0; k < kSeqsPerThread; ++k) {
     const int s = tid + k * kPlanThreads;
     if (s < a.NS && rank_of[k] >= 0) {
-      const int b = start[g_of[k]], n = cnt[g_of[k]];
+      const int g = G(k);
+      const int b = start[g], n = cnt[g];
       int place = rank_of[k];
       if (n <= 64) {
         place = 0;
-        for (int m = 0; m < n; ++m) place += members[b + m] < s;
+        for (int m = 0; m < n; ++m) place += (int)members[b + m] < s;
       }
       a.group_seqs[b + place] = s;
     }
@@ -341,13 +359,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
   }
 }
 
+constexpr int kSmallMaxSeqs = 8192, kSmallMaxGroups = 2048;
+constexpr int kMediumMaxSeqs = 32768, kMediumMaxGroups = 8192;
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel_small(AttnArgs a) {
+  plan_in_lds<kSmallMaxSeqs, kSmallMaxGroups, int>(a);
+}
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel_medium(AttnArgs a) {
+  plan_in_lds<kMediumMaxSeqs, kMediumMaxGroups, uint16_t>(a);
+}
+
 }  // namespace
 
 hipError_t launch_plan(const AttnArgs& a, hipStream_t st) {
-  const bool small = a.NS <= kSmallMaxSeqs && a.NG <= kSmallMaxGroups &&
-                     a.Cs / 32 <= kSmallMaxClasses && a.Cp / 32 <= kSmallMaxClasses;
-  if (small) hipLaunchKernelGGL(plan_kernel_small, dim3(1), dim3(kPlanThreads), 0, st, a);
-  else hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
+  const bool classes_fit = a.Cs / 32 <= kSmallMaxClasses && a.Cp / 32 <= kSmallMaxClasses;
+  if (classes_fit && a.NS <= kSmallMaxSeqs && a.NG <= kSmallMaxGroups)
+    hipLaunchKernelGGL(plan_kernel_small, dim3(1), dim3(kPlanThreads), 0, st, a);
+  else if (classes_fit && a.NS <= kMediumMaxSeqs && a.NG <= kMediumMaxGroups)
+    hipLaunchKernelGGL(plan_kernel_medium, dim3(1), dim3(kPlanThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
   return hipGetLastError();
 }
 

@@ -211,7 +211,6 @@ constexpr int kTpWaves = kTpThreads / 64;
 constexpr int kWin = 32768;                  // histogram window, in values (keys)
 constexpr int kTile = kTpThreads * 8;        // tokens per tile of pass 3
 constexpr int kLowestKey = 0x0080;           // key of the most negative finite bf16; below: -inf, NaN
-constexpr int kHighestKey = 0xff7f;          // key of the largest finite bf16; above: +inf, NaN
 
 __device__ __forceinline__ int key_of(uint32_t bits) {   // larger value <=> larger key; -0 counts as +0
   if ((bits & 0x7fffu) == 0) bits = 0;

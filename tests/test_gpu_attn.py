@@ -91,11 +91,12 @@ def test_big_groups_and_query_row_blocks(sizes):
     check_attn(inp, B.MARL_OUT_F32, prefix_chunk_tokens=64)
 
 
-def test_many_groups_use_the_general_plan_kernel():
-    """More groups than the LDS-resident plan kernel handles (2048)."""
-    print("case: many groups", flush=True)
+@pytest.mark.parametrize("NG", [2100, 8300])
+def test_many_groups_use_the_larger_plan_kernels(NG):
+    """More groups than the small LDS-resident plan kernel handles (2048), and more than the
+    larger one does (8192: the plan that works in global memory)."""
+    print("case: many groups", NG, flush=True)
     rng = np.random.default_rng(21)
-    NG = 2100
     sizes = rng.integers(1, 3, NG)
     gos = np.repeat(np.arange(NG), sizes)
     inp = custom_inputs(rng.integers(0, 40, NG), rng.integers(0, 50, len(gos)), gos, 4, 2, seed=23)

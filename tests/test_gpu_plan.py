@@ -91,16 +91,33 @@ def test_plan_large_group_stays_a_valid_set():
     assert sorted(got["seqs"][100:]) == sorted(np.nonzero(gos == 1)[0])
 
 
-def test_plan_general_kernel_for_shapes_beyond_the_lds_variant():
-    """More than 8192 sequences / 2048 groups: the plan kernel that keeps its bookkeeping in
-    global memory runs; same contract."""
-    print("case: plan big", flush=True)
-    rng = np.random.default_rng(11)
-    NG = 2500
-    sizes = rng.integers(1, 8, NG)
+def big_case(NG, lo, hi, seed):
+    rng = np.random.default_rng(seed)
+    sizes = rng.integers(lo, hi, NG)
     gos = rng.permutation(np.repeat(np.arange(NG), sizes)).astype(np.int32)
-    assert len(gos) > 8192
     pl = rng.integers(0, 400, NG).astype(np.int32)
     sl = rng.integers(0, 700, len(gos)).astype(np.int32)
     shape = B.make_shape(len(gos), NG, 8, 2, 10, 25, 44, suffix_chunk_tokens=256, prefix_chunk_tokens=128)
+    return shape, pl, sl, gos
+
+
+def test_plan_larger_lds_variant():
+    """8193 .. 32768 sequences in up to 8192 groups: the LDS-resident plan with 16-bit member ids."""
+    print("case: plan medium", flush=True)
+    shape, pl, sl, gos = big_case(2500, 1, 8, 11)
+    assert 8192 < len(gos) <= 32768
+    compare(shape, pl, sl, gos, 8, 2)
+    shape, pl, sl, gos = big_case(8192, 4, 5, 12)        # exactly 32768 sequences in 8192 groups
+    assert len(gos) == 32768
+    compare(shape, pl, sl, gos, 8, 2)
+
+
+def test_plan_general_kernel_for_shapes_beyond_the_lds_variants():
+    """More than 32768 sequences or 8192 groups: the plan kernel that keeps its bookkeeping in
+    global memory runs; same contract."""
+    print("case: plan big", flush=True)
+    shape, pl, sl, gos = big_case(8300, 1, 3, 13)        # too many groups
+    compare(shape, pl, sl, gos, 8, 2)
+    shape, pl, sl, gos = big_case(4000, 8, 10, 14)       # too many sequences
+    assert len(gos) > 32768
     compare(shape, pl, sl, gos, 8, 2)
