@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0
 # (profiles/decode_step_qwen7b_hbm_counters.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors a copy kernel of known size gives).  Valid only for the kernel source it was taken
 # with: reported as null when the source has changed since.
-SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5527.0e6 + 29.0e6,
-                  "kernel_sources_sha256": "8d4958473408b1810e339e3104bb8242042eee7aaf8d74408005a7d41dc640ed"}
+SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5527.2e6 + 29.0e6,
+                  "kernel_sources_sha256": "050ca3405763654f32fdd8d7df71bbc1d364241e3417d7e019a6b67ed389c6c4"}
 SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 

@@ -32,12 +32,16 @@ namespace {
 
 constexpr int kWaves = kAttnThreads / 64;
 
-// LDS per workgroup: (max, sum) of every wave and one buffer for a wave's accumulators.
+// LDS per workgroup for the cross-wave combine: (max, sum) and the row index of every q-row, and
+// every wave's accumulators in row-major order (a row is 128 floats, padded to 132 so that the
+// 16 rows a wave instruction writes start in different banks).
+constexpr int kAccRowFloats = kD + 4;
 template <int MT>
 struct ItemLds {
   float m[kWaves][MT * 16];
   float l[kWaves][MT * 16];
-  f32x4 acc[MT * 8 * 64];
+  int row[MT * 16];
+  __attribute__((aligned(16))) float acc[kWaves][MT * 16][kAccRowFloats];
 };
 
 // Processes tokens [tok_begin, tok_end) of one block-table row for MT tiles of query rows
@@ -209,60 +213,49 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
     l_run[qt] = rows_allreduce_sum(l_run[qt]);
   }
 
-  float m_all[MT], l_all[MT];
-#pragma unroll
-  for (int qt = 0; qt < MT; ++qt) {
-    m_all[qt] = m_run[qt];
-    l_all[qt] = l_run[qt];
-  }
   if constexpr (NW > 1) {
-    // combine the waves in a fixed order: every wave rescales to the common max, then waves
-    // 1..3 hand their accumulators to wave 0 one after the other
+    // Combine the waves: every wave puts its (max, sum) and its accumulators, row-major, into
+    // LDS; after one barrier all threads share the 16 x 128 outputs, each computing a float4 as
+    // the sum over the waves in wave order (fixed order: bit-identical reruns) rescaled to the
+    // common max, and the workgroup writes every row's 512 bytes as full cache lines.
+    static_assert(MT == 1, "the workgroup-wide combine handles one 16-row tile");
     if (j == 0) {
-#pragma unroll
-      for (int qt = 0; qt < MT; ++qt) {
-        lds.m[wave][qt * 16 + i] = m_run[qt];
-        lds.l[wave][qt * 16 + i] = l_run[qt];
-      }
+      lds.m[wave][i] = m_run[0];
+      lds.l[wave][i] = l_run[0];
+      if (wave == 0) lds.row[i] = row_index[0];
     }
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+      *reinterpret_cast<f32x4*>(&lds.acc[wave][i][16 * ct + 4 * j]) = acc[0][ct];
     __syncthreads();
+    constexpr int kPerThread = 16 * (kD / 4) / (NW * 64);   // float4 outputs per thread
 #pragma unroll
-    for (int qt = 0; qt < MT; ++qt) {
-      float mm = lds.m[0][qt * 16 + i];
+    for (int k = 0; k < kPerThread; ++k) {
+      const int e = threadIdx.x + k * NW * 64;
+      const int r = e / (kD / 4), c4 = e % (kD / 4);
+      const int ridx = lds.row[r];
+      if (ridx >= 0) {
+        float mm = lds.m[0][r];
 #pragma unroll
-      for (int w = 1; w < NW; ++w) mm = fmaxf(mm, lds.m[w][qt * 16 + i]);
-      float ll = 0.f;
+        for (int w = 1; w < NW; ++w) mm = fmaxf(mm, lds.m[w][r]);
+        float ll = 0.f;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        const float mw = lds.m[w][qt * 16 + i];
-        const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
-        ll += lds.l[w][qt * 16 + i] * f;
+        for (int w = 0; w < NW; ++w) {
+          const float mw = lds.m[w][r];
+          const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
+          ll += lds.l[w][r] * f;
+          o += *reinterpret_cast<const f32x4*>(&lds.acc[w][r][4 * c4]) * f;
+        }
+        const size_t ps = (size_t)ridx * nslot + slot;
+        *reinterpret_cast<f32x4*>(a.partial_o + ps * kD + 4 * c4) = o;
+        if (c4 == 0) a.partial_ml[ps] = make_float2(mm, ll);
       }
-      m_all[qt] = mm;
-      l_all[qt] = ll;
-      const float f_own = (m_run[qt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[qt] - mm);
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= f_own;
     }
-    for (int w = 1; w < NW; ++w) {
-      if (wave == w) {
-#pragma unroll
-        for (int qt = 0; qt < MT; ++qt)
-#pragma unroll
-          for (int ct = 0; ct < 8; ++ct) lds.acc[(qt * 8 + ct) * 64 + lane] = acc[qt][ct];
-      }
-      __syncthreads();
-      if (wave == 0) {
-#pragma unroll
-        for (int qt = 0; qt < MT; ++qt)
-#pragma unroll
-          for (int ct = 0; ct < 8; ++ct) acc[qt][ct] += lds.acc[(qt * 8 + ct) * 64 + lane];
-      }
-      __syncthreads();
-    }
-  }
-
-  if (wave == 0) {   // with NW = 1 every wave is its own "wave 0"
+    // the next use of this LDS comes after the workgroup's next trip to the work queue, which
+    // has barriers of its own
+  } else {
+    // one wave on its own: lane (i, j) holds channels 16*ct + 4*j .. +3 of q-row i
 #pragma unroll
     for (int qt = 0; qt < MT; ++qt) {
       if (row_index[qt] >= 0) {
@@ -270,7 +263,7 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
         float* dst = a.partial_o + ps * kD + 4 * j;
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct];
-        if (j == 0) a.partial_ml[ps] = make_float2(m_all[qt], l_all[qt]);
+        if (j == 0) a.partial_ml[ps] = make_float2(m_run[qt], l_run[qt]);
       }
     }
   }
