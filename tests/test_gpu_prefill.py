@@ -197,3 +197,38 @@ def test_overlapping_groups_cannot_overrun_the_item_list():
     got = run_gpu(replace(a, prefix_block_table=tab, q_start=qs), B.MARL_OUT_F32, expect_flags=B.FLAG_BAD_GROUP)
     want, want_abs = reference(a)
     assert (np.abs(got - want) <= 1e-3 + 2.0 ** -8 * want_abs).all()
+
+
+def test_full_size_prompts_of_the_bench_workload_sampled_rows():
+    """The prompts bench.py's prefill leg runs (256 prompts of the qwen7b workload, 329 k tokens),
+    in the same launch configuration; sampled query rows are checked one by one with the C decode
+    checker on a compact copy of the pages that row sees."""
+    w = I.WORKLOADS["qwen7b"]
+    lens = I.draw_lengths(w, np.random.default_rng(w.seed)).prefix_lens.tolist()
+    inp = I.build_prefill_inputs(w.Hq, w.Hkv, lens, [0] * len(lens), device="cuda", seed=w.seed, poison=False)
+    shape, ws, out = B.prepare_prefill(inp, B.MARL_OUT_BF16)
+    B.run_prefill(inp, shape, ws, out)
+    torch.cuda.synchronize()
+    assert B.marl_attn_read_flags(ws) == 0
+    assert bool(torch.isfinite(out.float()).all())
+    qs = inp.q_start.cpu().numpy()
+    rng = np.random.default_rng(4)
+    longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
+    picks = [(longest, lens[longest] - 1), (longest, 0), (shortest, lens[shortest] - 1), (0, 17), (255, lens[255] // 2)] + \
+            [(int(g), int(rng.integers(0, lens[g]))) for g in rng.integers(0, len(lens), size=19)]
+    worst = 0.0
+    for g, tau in picks:
+        npages = tau // 16 + 1
+        pages = inp.prefix_block_table[g, :npages].long()
+        kb, vb = I.bf16_bits(inp.k_pages[pages].cpu()), I.bf16_bits(inp.v_pages[pages].cpu())
+        qb = I.bf16_bits(inp.q[qs[g] + tau:qs[g] + tau + 1].cpu())
+        common = (np.arange(npages, dtype=np.int32)[None, :], np.zeros((1, 1), dtype=np.int32),
+                  np.array([tau + 1], dtype=np.int32), np.zeros(1, dtype=np.int32), np.zeros(1, dtype=np.int32),
+                  inp.scale, w.Hq, w.Hkv)
+        want = R.decode_attn(qb, kb, vb, *common)[0]
+        want_abs = R.decode_attn(qb, kb, vb & 0x7fff, *common)[0]
+        got = out[qs[g] + tau].float().cpu().numpy().astype(np.float64)
+        excess = np.abs(got - want) - (1e-3 + 2.0 ** -7 * want_abs)
+        assert excess.max() <= 0, (g, tau, excess.max())
+        worst = max(worst, float(np.abs(got - want).max()))
+    print("prefill full size: worst |delta| over sampled rows", worst, flush=True)
