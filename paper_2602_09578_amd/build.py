@@ -21,7 +21,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
 # (masked scores are -inf, unused value slots are cleared as integers), so the compiler may drop
 # the canonicalising v_max it otherwise puts in front of every maximum of a matrix-core result:
 # the vector ALU is the busiest unit of the attention kernels.  Host code keeps its NaN checks.
-FILE_FLAGS = {"prefill_kernels.hip": ["-Xarch_device", "-fno-honor-nans"]}
+_NO_NANS = ["-Xarch_device", "-fno-honor-nans"]
+FILE_FLAGS = {"prefill_kernels.hip": _NO_NANS, "attn_kernels.hip": _NO_NANS}
 
 
 def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PATH) -> str:

@@ -9,6 +9,8 @@
 //   in which the cumulative probability passes u, an ordered scan inside that chunk finds the
 //   token.  Token = first t with sum_{v <= t} p_v > u; if rounding leaves none, the last token
 //   with non-zero probability.
+#include <type_traits>
+
 #include "marl_internal.h"
 
 namespace marl {
@@ -194,8 +196,10 @@ __global__ __launch_bounds__(64) void sample_pick_kernel(SampleArgs a) {
 // tokens at the threshold value": the kernel finds the threshold with an exact counting
 // histogram over the values instead of sorting 150 k tokens.
 //
-// One workgroup of 1024 threads owns a row and makes these passes over it (the row is re-read
-// from the caches / HBM, 16-byte loads):
+// One workgroup of 1024 threads owns a row and makes these passes over it.  Rows of up to
+// kTpRegTiles * 8192 logits (163840: the vocabularies in use) are read from memory ONCE and kept
+// in registers, 16 bytes per thread and tile; longer rows are re-read from the caches / HBM for
+// every pass (16-byte loads):
 //   1. maximum value and Z = sum 2^(y - M)  (running (max, sum) per thread, fixed-order merge);
 //   2. count histogram in LDS over the 32768 values just below the maximum (order-preserving
 //      16-bit key of the bf16 pattern; integer LDS atomics, so the result does not depend on
@@ -211,6 +215,8 @@ constexpr int kTpWaves = kTpThreads / 64;
 constexpr int kWin = 32768;                  // histogram window, in values (keys)
 constexpr int kTile = kTpThreads * 8;        // tokens per tile of pass 3
 constexpr int kLowestKey = 0x0080;           // key of the most negative finite bf16; below: -inf, NaN
+constexpr int kTpRegTiles = 20;              // tiles of a row that the register-resident variant holds
+constexpr int kScanStep = 4;                 // scan positions per thread and round of the threshold search
 
 __device__ __forceinline__ int key_of(uint32_t bits) {   // larger value <=> larger key; -0 counts as +0
   if ((bits & 0x7fffu) == 0) bits = 0;
@@ -324,7 +330,41 @@ __device__ __forceinline__ void sweep_row(const uint16_t* x, long V, int tid, F&
 __device__ __forceinline__ float lo_val(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_val(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-__global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
+// Sum over the 64 lanes, result in every lane, inside the vector ALU: four DPP steps all-reduce
+// each row of 16 lanes (swap neighbours, swap pairs, mirror the halves of 8, mirror the row),
+// two row swaps combine the four rows.  (A shuffle-based reduction keeps six lane-address
+// registers alive and goes through the LDS crossbar twelve times per call.)
+template <class T>
+__device__ __forceinline__ T wave_allreduce_sum(T v) {
+  static_assert(sizeof(T) == 4, "32-bit values");
+  auto dpp = [](T x, auto ctrl_tag) {
+    constexpr int ctrl = decltype(ctrl_tag)::value;
+    return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xf, 0xf, false));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1, 0, 3, 2]
+  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2, 3, 0, 1]
+  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  // (the swap results are copied to scalars first: a bit cast applied directly to an element of
+  // the returned vector reads element 0 for both)
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const uint32_t a0 = a[0], a1 = a[1];
+  v = __builtin_bit_cast(T, a0) + __builtin_bit_cast(T, a1);
+  const uint32_t w = __builtin_bit_cast(uint32_t, v);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  const uint32_t b0 = b[0], b1 = b[1];
+  return __builtin_bit_cast(T, b0) + __builtin_bit_cast(T, b1);
+}
+
+// a value that is the same in every lane, moved to a scalar register (frees a vector register)
+__device__ __forceinline__ float uniform_f(float v) { return __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(v))); }
+__device__ __forceinline__ int uniform_i(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// NT > 0: the row's tiles live in NT 16-byte registers per thread (vocab <= NT * kTile);
+// NT = 0: every pass reads the row from memory.
+template <int NT>
+__device__ __forceinline__ void sample_top_p_body(const TopPArgs& a) {
   __shared__ TpShared sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x;
@@ -332,11 +372,38 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
   const float c = a.inv_temp_log2e;
   const long V = a.vocab;
   const int ntiles = (int)((V + kTile - 1) / kTile);
+  u32x4 held[NT > 0 ? NT : 1];
+  if constexpr (NT > 0) {
+    // every load is issued before the first use: NT * 16 bytes per thread in flight
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      held[t] = u32x4{0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u};   // -inf
+      if (t < ntiles) held[t] = load8_words(x, (long)t * kTile + (long)tid * 8, V);
+    }
+  }
+  // one pass over the row in tile order: fn(tile, this thread's 8 tokens of the tile as 4 words)
+  auto sweep = [&](auto&& fn) {
+    if constexpr (NT > 0) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        if (t < ntiles) {   // workgroup-uniform
+          // a copy whose value the compiler cannot trace back to the held row: otherwise it
+          // hoists per-token results of a pass (the 8 * NT keys) out of the loops around the
+          // pass and keeps them in scratch memory
+          u32x4 v = held[t];
+          asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+          fn(t, v);
+        }
+      }
+    } else {
+      sweep_row(x, V, tid, fn);
+    }
+  };
 
   // ---- pass 1: largest value and Z relative to it, in one sweep -------------------------------
   // per thread a running (largest y so far, sum relative to it); merged in thread order
   float xrun = -INFINITY, mrun = -INFINITY, zrun = 0.f;   // largest raw logit, the same times c, sum
-  sweep_row(x, V, tid, [&](int, u32x4 v) {
+  sweep([&](int, u32x4 v) {
     float r[8];
 #pragma unroll
     for (int d = 0; d < 4; ++d) { r[2 * d] = lo_val(v[d]); r[2 * d + 1] = hi_val(v[d]); }
@@ -361,7 +428,8 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < kTpWaves; ++w) xmax = fmaxf(xmax, sh.wave_m[w]);
-  const float M = xmax * c;
+  xmax = uniform_f(xmax);
+  const float M = uniform_f(xmax * c);
   double ztot;
   block_excl_scan_d(xrun > -INFINITY ? (double)zrun * (double)ex2(mrun - M) : 0.0, ztot, sh);
   const double Z = ztot;
@@ -389,7 +457,7 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
       __syncthreads();
       const int lo_eff = max(lo, kLowestKey);
       const unsigned span = (unsigned)(hi - lo_eff);
-      sweep_row(x, V, tid, [&](int, u32x4 v) {
+      sweep([&](int, u32x4 v) {
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           const int k0 = key_of(v[d] & 0xffffu), k1 = key_of(v[d] >> 16);
@@ -398,68 +466,77 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
         }
       });
       __syncthreads();
-      // position j of the scan is the value hi - j; thread t owns j = 32 t .. 32 t + 31
-      constexpr int kPer = kWin / kTpThreads;
-      auto mass_at = [&](int q) {
-        const int key = hi - (tid * kPer + q);
+      // Position j of the scan is the value hi - j.  The window is scanned in rounds of
+      // kScanStep positions per thread (thread t owns j = base + kScanStep t .. + kScanStep - 1)
+      // and the scan stops at the round in which the cumulative mass reaches tau: for peaked
+      // rows that is the first round, a few hundred values below the maximum.
+      auto mass_at = [&](int pos) {
+        const int key = hi - pos;
         const uint32_t cnt = sh.hist[key - lo];
         return cnt ? (double)cnt * (double)weight(key) : 0.0;
       };
-      double mine = 0.0;
-#pragma unroll 4
-      for (int q = 0; q < kPer; ++q) mine += mass_at(q);
-      double window_total;
-      const double before = above + block_excl_scan_d(mine, window_total, sh);
-      // first scan position at which the cumulative mass reaches tau: every thread at or past
-      // the crossing proposes its first such position, the smallest wins (robust against the
-      // last-bit differences between neighbouring threads' scan values)
-      int my_pos = kWin;
-      double my_above = 0.0;
-      if (before + mine >= tau) {
-        double run = before;
+      double window_total = 0.0;
+      for (int base = 0; base < kWin; base += kScanStep * kTpThreads) {
+        const int p0 = base + tid * kScanStep;
+        double mine = 0.0;
+#pragma unroll
+        for (int q = 0; q < kScanStep; ++q) mine += mass_at(p0 + q);
+        double round_total;
+        const double before = above + window_total + block_excl_scan_d(mine, round_total, sh);
+        // first scan position at which the cumulative mass reaches tau: every thread at or past
+        // the crossing proposes its first such position, the smallest wins (robust against the
+        // last-bit differences between neighbouring threads' scan values)
+        int my_pos = kWin;
+        double my_above = 0.0;
+        if (before + mine >= tau) {
+          double run = before;
 #pragma unroll 1
-        for (int q = 0; q < kPer; ++q) {
-          const double m = mass_at(q);
-          if (m > 0.0 && run + m >= tau) { my_pos = tid * kPer + q; my_above = run; break; }
-          run += m;
+          for (int q = 0; q < kScanStep; ++q) {
+            const double m = mass_at(p0 + q);
+            if (m > 0.0 && run + m >= tau) { my_pos = p0 + q; my_above = run; break; }
+            run += m;
+          }
+          if (my_pos < kWin) atomicMin(&sh.found_at, my_pos);
         }
-        if (my_pos < kWin) atomicMin(&sh.found_at, my_pos);
+        __syncthreads();
+        if (my_pos < kWin && my_pos == sh.found_at) {
+          const int key = hi - my_pos;
+          sh.thr_key = key;
+          sh.thr_cnt = (int)sh.hist[key - lo];
+          sh.thr_above = my_above;
+        }
+        __syncthreads();
+        if (sh.found_at < kWin) break;        // workgroup-uniform
+        window_total += round_total;
       }
-      __syncthreads();
-      if (my_pos < kWin && my_pos == sh.found_at) {
-        const int key = hi - my_pos;
-        sh.thr_key = key;
-        sh.thr_cnt = (int)sh.hist[key - lo];
-        sh.thr_above = my_above;
-      }
-      __syncthreads();
       if (sh.found_at < kWin) break;          // workgroup-uniform
       above += window_total;
     }
   }
   __syncthreads();
-  const int thr_key = sh.thr_key;
+  const int thr_key = uniform_i(sh.thr_key);
   // how many of the threshold-value tokens (in index order) the nucleus takes
   int ties_kept = 0;
   float thr_w = 0.f;
   double nucleus = Z;
   if (thr_key >= 0) {
-    thr_w = weight(thr_key);
+    thr_w = uniform_f(weight(thr_key));
     const double need = ((double)a.top_p * Z - sh.thr_above) / (double)thr_w;
-    ties_kept = (int)fmin(fmax(ceil(need), 1.0), (double)sh.thr_cnt);
+    ties_kept = uniform_i((int)fmin(fmax(ceil(need), 1.0), (double)sh.thr_cnt));
     nucleus = sh.thr_above + (double)ties_kept * (double)thr_w;
   }
-  const float target = (float)((double)a.uniforms[row] * nucleus);
+  const float target = uniform_f((float)((double)a.uniforms[row] * nucleus));
   // pass 3 compares raw logit values (every bf16 is exact in float; -0 == +0 as in the keys);
   // with no threshold every finite logit is above it
-  const float thr_x = thr_key >= 0 ? value_of_key(thr_key) : -INFINITY;
+  const float thr_x = uniform_f(thr_key >= 0 ? value_of_key(thr_key) : -INFINITY);
+  const float log2_Z = uniform_f(__builtin_amdgcn_logf((float)Z));
 
   // ---- pass 3: inverse CDF over the nucleus in index order ----------------------------------
   // per tile and wave: mass of the tokens above the threshold, number of tokens at it
   float* part_m = reinterpret_cast<float*>(sh.hist);             // [ntiles][kTpWaves]
   int* part_n = reinterpret_cast<int*>(sh.hist) + kWin / 2;      // [ntiles][kTpWaves]
   __syncthreads();                                               // the histogram is no longer read
-  sweep_row(x, V, tid, [&](int t, u32x4 v) {
+  sweep([&](int t, u32x4 v) {
     float m8 = 0.f;
     int n8 = 0;
 #pragma unroll
@@ -470,9 +547,8 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
       m8 += r1 > thr_x ? w1 : 0.f;
       n8 += (r0 == thr_x) + (r1 == thr_x);
     }
-    m8 = wave_sum(m8);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) n8 += __shfl_xor(n8, d);
+    m8 = wave_allreduce_sum(m8);
+    n8 = wave_allreduce_sum(n8);
     if (lane == 0) { part_m[t * kTpWaves + wave] = m8; part_n[t * kTpWaves + wave] = n8; }
   });
   __syncthreads();
@@ -505,7 +581,15 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
   {
     const int t = sh.tile;
     const long pos = (long)t * kTile + (long)tid * 8;
-    const u32x4 v = load8_words(x, pos, V);
+    u32x4 v;
+    if constexpr (NT > 0) {
+      v = held[0];
+#pragma unroll
+      for (int u = 1; u < NT; ++u)
+        if (u == t) v = held[u];
+    } else {
+      v = load8_words(x, pos, V);
+    }
     float r[8];
 #pragma unroll
     for (int d = 0; d < 4; ++d) { r[2 * d] = lo_val(v[d]); r[2 * d + 1] = hi_val(v[d]); }
@@ -553,10 +637,13 @@ __global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) {
 #pragma unroll
       for (int e = 1; e < 8; ++e) if (e == e_pick) r_pick = r[e];
       a.out_tokens[row] = (int)(pos + e_pick);
-      a.out_logprobs[row] = (__builtin_fmaf(r_pick, c, -M) - __builtin_amdgcn_logf((float)Z)) * 0.69314718055994530942f;
+      a.out_logprobs[row] = (__builtin_fmaf(r_pick, c, -M) - log2_Z) * 0.69314718055994530942f;
     }
   }
 }
+
+__global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel(TopPArgs a) { sample_top_p_body<kTpRegTiles>(a); }
+__global__ __launch_bounds__(kTpThreads) void sample_top_p_kernel_long(TopPArgs a) { sample_top_p_body<0>(a); }
 
 }  // namespace
 
@@ -566,7 +653,10 @@ int top_p_max_vocab() { return (kWin / 2 / kTpWaves) * kTile; }   // tile sums m
 
 hipError_t launch_sample_top_p(const TopPArgs& a, hipStream_t st) {
   if (a.rows == 0) return hipSuccess;
-  hipLaunchKernelGGL(sample_top_p_kernel, dim3((unsigned)a.rows), dim3(kTpThreads), 0, st, a);
+  if (a.vocab <= kTpRegTiles * kTile)
+    hipLaunchKernelGGL(sample_top_p_kernel, dim3((unsigned)a.rows), dim3(kTpThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL(sample_top_p_kernel_long, dim3((unsigned)a.rows), dim3(kTpThreads), 0, st, a);
   return hipGetLastError();
 }
 
