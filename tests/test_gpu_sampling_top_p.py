@@ -62,7 +62,9 @@ def check(logits: torch.Tensor, u: np.ndarray, T: float, top_p: float, rows_to_c
 @pytest.mark.parametrize("rows,vocab,T,top_p", [
     (16, 4096, 1.0, 0.9), (12, 152064, 1.0, 0.95), (3, 152064, 0.6, 0.5), (100, 32000, 1.7, 0.8),
     (7, 4099, 1.0, 0.99), (5, 7, 1.0, 0.6), (2, 1, 1.0, 0.3), (9, 20481, 0.9, 0.1), (6, 8192, 1.0, 1.0),
-    (6, 8193, 1.3, 1e-4)])
+    (6, 8193, 1.3, 1e-4),
+    # rows longer than the register-resident variant holds (163840 logits): every pass re-reads memory
+    (3, 200003, 1.0, 0.9), (2, 262144, 0.7, 0.97)])
 def test_tokens_match_the_reference(rows, vocab, T, top_p):
     print("case: top-p", rows, vocab, T, top_p, flush=True)
     lp = I.build_logprob_inputs(rows, vocab, 3.0, 31, temperature=T)
@@ -91,6 +93,13 @@ def test_flat_rows_ties_and_masks():
     x[2, :] = float("-inf")
     tok, out = run(x, np.array([0.0, 0.9999999, 0.5]), 1.0, 0.5)  # 3900 equal tokens, half of them kept
     assert tok[0] == 100 and abs(tok[1] - (100 + 1949)) <= 1 and tok[2] == -1 and np.isnan(out[2])
+    # the same on a row that is re-read from memory for every pass
+    V2 = 170000
+    flat2 = torch.full((2, V2), -1.25, dtype=torch.bfloat16)
+    u2 = np.array([0.25003, 0.99996])
+    tok, out = run(flat2, u2, 1.0, 0.3)
+    assert np.abs(tok - np.floor(u2.astype(np.float32).astype(np.float64) * 51000)).max() <= 1
+    assert tok.max() < 51001 and np.abs(out + np.log(V2)).max() <= 1e-3
     # +0 and -0 are different bit patterns of the same probability: they tie, by index
     z = torch.zeros(2, 1000, dtype=torch.bfloat16); z[:, ::2] = -0.0
     tok, _ = run(z, np.array([0.5003, 0.99996]), 1.0, 0.25)
