@@ -30,8 +30,8 @@ HBM_PEAK_GBPS = 8000.0
 # factors a copy kernel of known size gives).  Valid only for the kernel source it was taken
 # with: reported as null when the source has changed since.
 SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5527.2e6 + 29.0e6,
-                  "kernel_sources_sha256": "050ca3405763654f32fdd8d7df71bbc1d364241e3417d7e019a6b67ed389c6c4"}
-SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
+                  "kernel_sources_sha256": "ef5f0bb71015b1cb9ea21cb02a523a922226a7660a3a9a8232d5bf52926cc68d"}
+SUFFIX_SOURCES = ("csrc/attn_kernels.hip", "csrc/wave_ops.h", "build.py")   # sources and compiler flags
 
 
 def suffix_traffic(workload: str):
@@ -39,7 +39,7 @@ def suffix_traffic(workload: str):
     h = hashlib.sha256()
     try:
         for name in SUFFIX_SOURCES:
-            h.update(open(os.path.join(ROOT, "paper_2602_09578_amd", "csrc", name), "rb").read())
+            h.update(open(os.path.join(ROOT, "paper_2602_09578_amd", name), "rb").read())
     except OSError:
         return None
     if workload != SUFFIX_TRAFFIC["workload"] or h.hexdigest() != SUFFIX_TRAFFIC["kernel_sources_sha256"]:
