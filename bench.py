@@ -231,6 +231,30 @@ def main():
                       "frac_of_bf16_mfma_peak": pf_flops / (t_attn / 5 * 1e-3) / 1e12 / 2500.0,
                       "kv_write_prompt_us": t_write / 5 * 1e3}
     del pf, pws, pout
+    # weight synchronisation as one copy: a parameter list of the workload's model shape (bf16)
+    # gathered into one contiguous buffer by one launch, against one device copy per parameter
+    params = [torch.zeros(n, dtype=torch.bfloat16, device=dev) for n in I.model_param_sizes(w.Hq, w.Hkv, vocab)]
+    table = B.PackTable(params)
+    packed = torch.empty(table.packed_bytes, dtype=torch.uint8, device=dev)
+    views = [packed[o:o + p_.numel() * 2].view(torch.bfloat16) for o, p_ in zip(table.offsets, params)]
+    t_pack = t_each = 0.0
+    for it in range(5):
+        ev0.record()
+        B.marl_pack_tensors(table, packed)
+        ev1.record()
+        ev2 = torch.cuda.Event(enable_timing=True)
+        for v_, p_ in zip(views, params):
+            v_.copy_(p_)
+        ev2.record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            t_pack += ev0.elapsed_time(ev1)
+            t_each += ev1.elapsed_time(ev2)
+    moved = sum(p_.numel() * 2 for p_ in params)
+    res["weight_pack"] = {"ms_per_call": t_pack / 3, "tensors": len(params), "bytes": moved,
+                          "GBps_read_plus_write": 2 * moved / (t_pack / 3 * 1e-3) / 1e9,
+                          "one_copy_per_tensor_ms": t_each / 3}
+    del params, packed, views, table
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
     print(json.dumps(res))

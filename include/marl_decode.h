@@ -368,6 +368,42 @@ int marl_balancer_request_state(const marl_balancer* b, int32_t request_id, int3
                                 int32_t* generated, int64_t* done_step);
 
 /*
+ * Weight synchronisation as ONE copy (the paper's Discussion, "Hardware-Aware Abstraction":
+ * updating a rollout engine parameter by parameter is dominated by the control plane, so the
+ * weights are aggregated into a single contiguous buffer and synchronised with O(1) operations
+ * instead of O(number of parameters)).  marl_pack_tensors gathers n tensors into one
+ * contiguous device buffer with a single kernel launch; marl_unpack_tensors scatters such a
+ * buffer back into n tensors.  Pure data movement, bit-exact.
+ *
+ * The caller describes the tensors in a table of marl_pack_entry that lives in DEVICE memory
+ * (it is read by the kernel; build it once per model and keep it):
+ *   ptr          device address of the tensor's first byte (any alignment; 16-byte aligned
+ *                tensors at 16-byte aligned offsets are moved with 16-byte accesses)
+ *   offset       where the tensor's bytes start in the packed buffer
+ *   bytes        size of the tensor
+ *   first_chunk  number of MARL_PACK_CHUNK_BYTES pieces of all earlier entries:
+ *                first_chunk[0] = 0, first_chunk[i+1] = first_chunk[i] + ceil(bytes[i] / chunk)
+ * marl_pack_plan fills offset (tensors in table order, each start rounded up to 256 bytes) and
+ * first_chunk of a HOST copy of the table from its ptr/bytes fields and returns the packed size
+ * and the total chunk count, which the two device calls take as arguments.
+ * Tensors and packed ranges must not overlap each other.  Errors: MARL_INVALID_ARG for null
+ * pointers with n > 0, negative counts, or a plan whose totals do not fit (more than 2^31 - 1
+ * chunks).  n = 0 is a no-op.
+ */
+#define MARL_PACK_CHUNK_BYTES 262144
+typedef struct {
+  void* ptr;
+  uint64_t offset;
+  uint64_t bytes;
+  uint64_t first_chunk;
+} marl_pack_entry;
+int marl_pack_plan(marl_pack_entry* entries_host, int32_t n, uint64_t* packed_bytes, int64_t* total_chunks);
+int marl_pack_tensors(const marl_pack_entry* entries, int32_t n, int64_t total_chunks, void* packed,
+                      void* stream);
+int marl_unpack_tensors(const marl_pack_entry* entries, int32_t n, int64_t total_chunks,
+                        const void* packed, void* stream);
+
+/*
  * Per-kernel timing of marl_decode_attn / marl_token_logprobs calls (for benchmarks).
  * After marl_profile_begin(max_calls) every call records HIP events around each of its
  * kernels on the call's stream (no synchronisation).  marl_profile_end() synchronises the

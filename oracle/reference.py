@@ -350,3 +350,35 @@ def kv_write_prompt(k_pages, v_pages, prefix_table, q_start, q_pos0, k_new, v_ne
             k_pages[page, :, slot, :] = k_new[tok]
             v_pages[page, :, :, slot] = v_new[tok]
     return k_pages, v_pages
+
+
+# ------------------------------------------------------------------------------------------
+# Weight synchronisation as one copy (the paper's Discussion, "Hardware-Aware Abstraction": the
+# weights are aggregated into a single contiguous buffer).  The definition written out: the
+# tensors' bytes one after the other in table order, every start rounded up to 256 bytes.
+# ------------------------------------------------------------------------------------------
+PACK_ALIGN = 256
+PACK_CHUNK = 262144
+
+
+def pack_layout(sizes):
+    """(offsets, first_chunk, packed_bytes, total_chunks) for tensors of the given byte sizes."""
+    offsets, first_chunk = [], []
+    off = chunks = 0
+    for n in sizes:
+        off = -(-off // PACK_ALIGN) * PACK_ALIGN
+        offsets.append(off)
+        first_chunk.append(chunks)
+        off += int(n)
+        chunks += -(-int(n) // PACK_CHUNK)
+    return offsets, first_chunk, off, chunks
+
+
+def pack_tensors(arrays, fill: int = 0):
+    """uint8 buffer holding every array's bytes at its offset; the gaps hold `fill`."""
+    raw = [np.ascontiguousarray(a).view(np.uint8).reshape(-1) for a in arrays]
+    offsets, _, total, _ = pack_layout([r.size for r in raw])
+    out = np.full(total, fill, dtype=np.uint8)
+    for r, o in zip(raw, offsets):
+        out[o:o + r.size] = r
+    return out, offsets

@@ -8,6 +8,7 @@ import os
 from dataclasses import dataclass
 from typing import Optional
 
+import numpy as np
 import torch
 
 from .build import LIB_PATH, build_library
@@ -52,6 +53,11 @@ class BalancerConfig(ctypes.Structure):
 
 class BalancerStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("now", "submitted", "completed", "migrations")]
+
+
+class PackEntry(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("offset", ctypes.c_uint64), ("bytes", ctypes.c_uint64),
+                ("first_chunk", ctypes.c_uint64)]
 
 
 class MarlError(RuntimeError):
@@ -111,6 +117,11 @@ def load_library(build_if_missing: bool = True):
     lib.marl_prefill_workspace_bytes.restype = lib.marl_prefill_attn.restype = ctypes.c_int
     lib.marl_kv_write_prompt.restype = ctypes.c_int
     lib.marl_grpo_advantages.restype = ctypes.c_int
+    PE = ctypes.POINTER(PackEntry)
+    lib.marl_pack_plan.argtypes = [PE, I32, ctypes.POINTER(ctypes.c_uint64), I64P]
+    lib.marl_pack_tensors.argtypes = [VP, I32, ctypes.c_int64, VP, VP]
+    lib.marl_unpack_tensors.argtypes = [VP, I32, ctypes.c_int64, VP, VP]
+    lib.marl_pack_plan.restype = lib.marl_pack_tensors.restype = lib.marl_unpack_tensors.restype = ctypes.c_int
     lib.marl_profile_begin.argtypes = [I32]
     lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
     for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_attn_plan",
@@ -366,6 +377,45 @@ class Balancer:
         _check(self._lib.marl_balancer_request_state(self._h, request_id, ctypes.byref(inst), ctypes.byref(gen),
                                                      ctypes.byref(done)), "marl_balancer_request_state")
         return int(inst.value), int(gen.value), int(done.value)
+
+
+class PackTable:
+    """The table marl_pack_tensors / marl_unpack_tensors read: planned on the host, kept on the device."""
+
+    def __init__(self, tensors):
+        self.n = len(tensors)
+        self.host = (PackEntry * max(self.n, 1))()
+        for k, t in enumerate(tensors):
+            self.host[k].ptr = t.data_ptr() if t.numel() else None
+            self.host[k].bytes = t.numel() * t.element_size()
+        nbytes, chunks = ctypes.c_uint64(0), ctypes.c_int64(0)
+        _check(load_library().marl_pack_plan(self.host, self.n, ctypes.byref(nbytes), ctypes.byref(chunks)),
+               "marl_pack_plan")
+        self.packed_bytes, self.total_chunks = nbytes.value, chunks.value
+        self.offsets = [self.host[k].offset for k in range(self.n)]
+        self.device = None
+        if self.n:
+            raw = np.frombuffer(bytes(self.host), dtype=np.uint8)[: self.n * ctypes.sizeof(PackEntry)].copy()
+            self.device = torch.from_numpy(raw).to(tensors[0].device)
+
+
+def marl_pack_tensors(table: PackTable, packed: torch.Tensor):
+    if table.n == 0:
+        return packed
+    _require_cuda(table.device, packed)
+    assert packed.numel() * packed.element_size() >= table.packed_bytes
+    _check(load_library().marl_pack_tensors(_ptr(table.device), table.n, table.total_chunks, _ptr(packed),
+                                            _stream(packed.device)), "marl_pack_tensors")
+    return packed
+
+
+def marl_unpack_tensors(table: PackTable, packed: torch.Tensor):
+    if table.n == 0:
+        return
+    _require_cuda(table.device, packed)
+    assert packed.numel() * packed.element_size() >= table.packed_bytes
+    _check(load_library().marl_unpack_tensors(_ptr(table.device), table.n, table.total_chunks, _ptr(packed),
+                                              _stream(packed.device)), "marl_unpack_tensors")
 
 
 def marl_profile_begin(max_calls: int):

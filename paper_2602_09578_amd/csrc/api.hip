@@ -595,6 +595,53 @@ int marl_grpo_advantages(const float* rewards, const int32_t* group_start, const
   return e == hipSuccess ? MARL_OK : hip_fail(e, "advantage kernel");
 }
 
+// ---- weight synchronisation as one copy ------------------------------------------------------
+int marl_pack_plan(marl_pack_entry* entries, int32_t n, uint64_t* packed_bytes, int64_t* total_chunks) {
+  if (n < 0 || !packed_bytes || !total_chunks || (n > 0 && !entries)) return MARL_INVALID_ARG;
+  uint64_t off = 0, chunks = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (entries[i].bytes > 0 && !entries[i].ptr) return MARL_INVALID_ARG;
+    off = (off + 255) & ~(uint64_t)255;
+    entries[i].offset = off;
+    entries[i].first_chunk = chunks;
+    if (entries[i].bytes > (uint64_t)1 << 46) return MARL_INVALID_ARG;
+    off += entries[i].bytes;
+    chunks += (entries[i].bytes + MARL_PACK_CHUNK_BYTES - 1) / MARL_PACK_CHUNK_BYTES;
+    if (chunks > 0x7fffffffull) return MARL_INVALID_ARG;
+  }
+  *packed_bytes = off;
+  *total_chunks = (int64_t)chunks;
+  return MARL_OK;
+}
+
+namespace {
+int pack_call(const marl_pack_entry* entries, int32_t n, int64_t total_chunks, void* packed, int unpack,
+              void* stream) {
+  if (n < 0 || total_chunks < 0 || total_chunks > 0x7fffffffll) return MARL_INVALID_ARG;
+  if (n == 0 || total_chunks == 0) return MARL_OK;
+  if (!entries || !packed) return MARL_INVALID_ARG;
+  std::call_once(g_dev_once, query_device);
+  if (g_dev_err != hipSuccess) return hip_fail(g_dev_err, "device query");
+  marl::PackArgs a;
+  a.entries = entries;
+  a.packed = static_cast<char*>(packed);
+  a.n = n;
+  a.total_chunks = (int32_t)total_chunks;
+  a.unpack = unpack;
+  const hipError_t e = marl::launch_pack(a, g_num_cus * 8, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MARL_OK : hip_fail(e, "pack kernel");
+}
+}  // namespace
+
+int marl_pack_tensors(const marl_pack_entry* entries, int32_t n, int64_t total_chunks, void* packed,
+                      void* stream) {
+  return pack_call(entries, n, total_chunks, packed, 0, stream);
+}
+int marl_unpack_tensors(const marl_pack_entry* entries, int32_t n, int64_t total_chunks,
+                        const void* packed, void* stream) {
+  return pack_call(entries, n, total_chunks, const_cast<void*>(packed), 1, stream);
+}
+
 // ---- profiling ----------------------------------------------------------------------------------
 int marl_profile_begin(int32_t max_calls) {
   if (max_calls < 1 || max_calls > (1 << 20)) return MARL_INVALID_ARG;

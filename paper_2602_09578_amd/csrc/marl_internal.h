@@ -79,6 +79,15 @@ struct KvCopyArgs {
 hipError_t launch_kv_append(const KvAppendArgs& a, hipStream_t st);
 hipError_t launch_kv_copy_pages(const KvCopyArgs& a, hipStream_t st);
 
+struct PackArgs {
+  const marl_pack_entry* entries;   // device
+  char* packed;
+  int32_t n;
+  int32_t total_chunks;
+  int32_t unpack;   // 0: tensors -> packed, 1: packed -> tensors
+};
+hipError_t launch_pack(const PackArgs& a, int grid, hipStream_t st);
+
 struct LogprobArgs {
   const uint16_t* logits;
   const int32_t* tokens;

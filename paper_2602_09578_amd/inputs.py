@@ -437,3 +437,20 @@ def build_prefill_inputs(Hq: int, Hkv: int, chunk_lens: Sequence[int], pos0: Seq
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
     return PrefillInputs(Hq, Hkv, num_pages, q, k_new, v_new, k_pages, v_pages, t(ptab), t(q_start),
                          t(p0.astype(np.int32)), scale=1.0 / math.sqrt(D))
+
+
+def model_param_sizes(Hq: int, Hkv: int, vocab: int, head_dim: int = 128):
+    """Element counts of the parameter tensors of a decoder of the workload's attention shape, in
+    checkpoint order: embedding, per layer (q, k, v projections with biases, output projection,
+    gate / up / down projections, two norms), final norm, output head.  Hidden size Hq * head_dim;
+    the layer count and MLP width are those of the 7B (Hq 28) and 32B (Hq 64 -> hidden 5120 there,
+    kept at Hq * head_dim here) members of the model family the paper trains; other shapes scale them."""
+    hidden = Hq * head_dim
+    kv = Hkv * head_dim
+    layers, mlp = (28, 18944) if Hq <= 28 else (64, 27648)
+    sizes = [vocab * hidden]
+    for _ in range(layers):
+        sizes += [hidden * hidden, hidden, kv * hidden, kv, kv * hidden, kv, hidden * hidden,
+                  mlp * hidden, mlp * hidden, hidden * mlp, hidden, hidden]
+    sizes += [hidden, vocab * hidden]
+    return sizes
