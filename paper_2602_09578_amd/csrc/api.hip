@@ -614,6 +614,9 @@ int marl_pack_plan(marl_pack_entry* entries, int32_t n, uint64_t* packed_bytes, 
   return MARL_OK;
 }
 
+#ifndef MARL_PACK_BLOCKS_PER_CU
+#define MARL_PACK_BLOCKS_PER_CU 2
+#endif
 namespace {
 int pack_call(const marl_pack_entry* entries, int32_t n, int64_t total_chunks, void* packed, int unpack,
               void* stream) {
@@ -628,7 +631,7 @@ int pack_call(const marl_pack_entry* entries, int32_t n, int64_t total_chunks, v
   a.n = n;
   a.total_chunks = (int32_t)total_chunks;
   a.unpack = unpack;
-  const hipError_t e = marl::launch_pack(a, g_num_cus * 8, static_cast<hipStream_t>(stream));
+  const hipError_t e = marl::launch_pack(a, g_num_cus * MARL_PACK_BLOCKS_PER_CU, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? MARL_OK : hip_fail(e, "pack kernel");
 }
 }  // namespace
