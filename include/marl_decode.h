@@ -368,6 +368,48 @@ int marl_balancer_request_state(const marl_balancer* b, int32_t request_id, int3
                                 int32_t* generated, int64_t* done_step);
 
 /*
+ * Page pool: the host-side bookkeeping of the paged KV cache (which physical pages are free,
+ * how many block-table rows refer to a page), with copy-on-write for samples that share pages.
+ * The paper's rollout engines keep the shared prompt once and let the samples of a prompt
+ * diverge (Parallel Sampling, Section 5.1); it leaves the mechanism to the inference backend,
+ * so the rules are stated here.  Host-only (no GPU call, no device memory); the caller owns
+ * the block tables as HOST int32 arrays, mirrors them to the device, and runs the copies this
+ * object asks for with marl_kv_copy_pages before the next marl_kv_append.
+ *
+ *   state   every page is free or has a reference count >= 1 (= the number of table entries,
+ *           over all rows the caller holds, that contain it).
+ *   alloc   takes n free pages, count 1 each; the free pages form a stack that initially pops
+ *           0, 1, 2, ... and receives released pages on top (last released, first reused).
+ *           If fewer than n pages are free nothing is taken: MARL_WORKSPACE_TOO_SMALL.
+ *   retain / release   +1 / -1 on each listed page; a page whose count reaches 0 is free again.
+ *           An id outside [0, num_pages), a free page, or (release) more releases in one call
+ *           than the page has references: MARL_INVALID_ARG and nothing is changed.
+ *   fork    the child row gets the ceil(len / 16) page ids of the parent row, each retained:
+ *           parent and child share every page, the partly filled last one included.
+ *   prepare_append   makes position `len` of a row writable for marl_kv_append and reports at
+ *           most one page copy: if len is a multiple of 16 a fresh page is put into
+ *           row[len / 16]; otherwise, if row[len / 16] is shared (count > 1), a fresh page
+ *           replaces it in the row, the old one is released, and (*copy_src, *copy_dst) =
+ *           (old, fresh) must be copied on the device before the append (copy-on-write: the
+ *           other holders keep the old page unchanged); otherwise nothing happens.  Without a
+ *           copy both are -1.  len >= max_pages * 16: MARL_INVALID_ARG; no free page:
+ *           MARL_WORKSPACE_TOO_SMALL (nothing changed).
+ *   drop    releases the ceil(len / 16) pages of a row (a finished sample).
+ */
+typedef struct marl_page_pool marl_page_pool;
+int marl_page_pool_create(int32_t num_pages, marl_page_pool** out);
+void marl_page_pool_destroy(marl_page_pool* p);
+int marl_page_pool_alloc(marl_page_pool* p, int32_t n, int32_t* pages_out);
+int marl_page_pool_retain(marl_page_pool* p, const int32_t* pages, int32_t n);
+int marl_page_pool_release(marl_page_pool* p, const int32_t* pages, int32_t n);
+int marl_page_pool_fork(marl_page_pool* p, const int32_t* parent_row, int32_t len, int32_t* child_row);
+int marl_page_pool_prepare_append(marl_page_pool* p, int32_t* row, int32_t max_pages, int32_t len,
+                                  int32_t* copy_src, int32_t* copy_dst);
+int marl_page_pool_drop(marl_page_pool* p, const int32_t* row, int32_t len);
+/* *refcount = 0 for a free page; *free_pages = number of free pages (either may be NULL) */
+int marl_page_pool_query(const marl_page_pool* p, int32_t page, int32_t* refcount, int32_t* free_pages);
+
+/*
  * Weight synchronisation as ONE copy (the paper's Discussion, "Hardware-Aware Abstraction":
  * updating a rollout engine parameter by parameter is dominated by the control plane, so the
  * weights are aggregated into a single contiguous buffer and synchronised with O(1) operations

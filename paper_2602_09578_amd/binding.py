@@ -117,6 +117,16 @@ def load_library(build_if_missing: bool = True):
     lib.marl_prefill_workspace_bytes.restype = lib.marl_prefill_attn.restype = ctypes.c_int
     lib.marl_kv_write_prompt.restype = ctypes.c_int
     lib.marl_grpo_advantages.restype = ctypes.c_int
+    lib.marl_page_pool_create.argtypes = [I32, ctypes.POINTER(VP)]
+    lib.marl_page_pool_destroy.argtypes = [VP]
+    lib.marl_page_pool_destroy.restype = None
+    lib.marl_page_pool_alloc.argtypes = [VP, I32, I32P]
+    lib.marl_page_pool_retain.argtypes = [VP, I32P, I32]
+    lib.marl_page_pool_release.argtypes = [VP, I32P, I32]
+    lib.marl_page_pool_fork.argtypes = [VP, I32P, I32, I32P]
+    lib.marl_page_pool_prepare_append.argtypes = [VP, I32P, I32, I32, I32P, I32P]
+    lib.marl_page_pool_drop.argtypes = [VP, I32P, I32]
+    lib.marl_page_pool_query.argtypes = [VP, I32, I32P, I32P]
     PE = ctypes.POINTER(PackEntry)
     lib.marl_pack_plan.argtypes = [PE, I32, ctypes.POINTER(ctypes.c_uint64), I64P]
     lib.marl_pack_tensors.argtypes = [VP, I32, ctypes.c_int64, VP, VP]
@@ -377,6 +387,61 @@ class Balancer:
         _check(self._lib.marl_balancer_request_state(self._h, request_id, ctypes.byref(inst), ctypes.byref(gen),
                                                      ctypes.byref(done)), "marl_balancer_request_state")
         return int(inst.value), int(gen.value), int(done.value)
+
+
+class PagePool:
+    """Host-side page bookkeeping (marl_page_pool_*).  Rows are numpy int32 arrays owned by the caller;
+    methods return the library's status code (0 = ok) so that error paths can be tested."""
+
+    def __init__(self, num_pages: int):
+        self._lib = load_library()
+        self._h = VP()
+        _check(self._lib.marl_page_pool_create(num_pages, ctypes.byref(self._h)), "marl_page_pool_create")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._lib.marl_page_pool_destroy(self._h)
+            self._h = None
+
+    @staticmethod
+    def _p(a: np.ndarray):
+        assert a.dtype == np.int32 and a.flags.c_contiguous
+        return a.ctypes.data_as(ctypes.POINTER(I32))
+
+    def alloc(self, n: int):
+        out = np.empty(max(n, 1), dtype=np.int32)
+        rc = self._lib.marl_page_pool_alloc(self._h, n, self._p(out))
+        return rc, (out[:n] if rc == 0 else None)
+
+    def retain(self, pages) -> int:
+        a = np.ascontiguousarray(pages, dtype=np.int32)
+        return self._lib.marl_page_pool_retain(self._h, self._p(a), len(a))
+
+    def release(self, pages) -> int:
+        a = np.ascontiguousarray(pages, dtype=np.int32)
+        return self._lib.marl_page_pool_release(self._h, self._p(a), len(a))
+
+    def fork(self, parent_row: np.ndarray, length: int, child_row: np.ndarray) -> int:
+        return self._lib.marl_page_pool_fork(self._h, self._p(parent_row), length, self._p(child_row))
+
+    def prepare_append(self, row: np.ndarray, length: int):
+        src, dst = I32(-1), I32(-1)
+        rc = self._lib.marl_page_pool_prepare_append(self._h, self._p(row), len(row), length, ctypes.byref(src),
+                                                     ctypes.byref(dst))
+        return rc, src.value, dst.value
+
+    def drop(self, row: np.ndarray, length: int) -> int:
+        return self._lib.marl_page_pool_drop(self._h, self._p(row), length)
+
+    def refcount(self, page: int) -> int:
+        c = I32(0)
+        _check(self._lib.marl_page_pool_query(self._h, page, ctypes.byref(c), None), "marl_page_pool_query")
+        return c.value
+
+    def free_pages(self) -> int:
+        c = I32(0)
+        _check(self._lib.marl_page_pool_query(self._h, 0, None, ctypes.byref(c)), "marl_page_pool_query")
+        return c.value
 
 
 class PackTable:

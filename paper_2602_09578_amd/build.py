@@ -12,7 +12,7 @@ CSRC = os.path.join(_PKG, "csrc")
 LIB_DIR = os.path.join(_PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libmarl_decode.so")
 SOURCES = ["api.hip", "plan_kernel.hip", "attn_kernels.hip", "merge_kernel.hip", "logprob_kernels.hip",
-           "kv_cache_kernels.hip", "sample_kernels.hip", "grpo_kernels.hip", "prefill_kernels.hip", "balancer.hip", "pack_kernels.hip"]
+           "kv_cache_kernels.hip", "sample_kernels.hip", "grpo_kernels.hip", "prefill_kernels.hip", "balancer.hip", "pack_kernels.hip", "page_pool.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
