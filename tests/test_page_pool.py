@@ -134,3 +134,79 @@ def test_library_by_hand_and_argument_errors():
     assert lib.marl_page_pool_create(0, None) == -1
     assert lib.marl_page_pool_alloc(None, 1, None) == -1
     assert lib.marl_page_pool_query(None, 0, None, None) == -1
+
+
+def test_page_pool_host_code_runs_clean_under_asan_ubsan(tmp_path):
+    """The pool is host C++: built alone with g++ and the sanitizers, a seeded trace (valid and
+    invalid calls) runs clean and ends with the reference's counts."""
+    import os, subprocess, sys, textwrap
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib = tmp_path / "libpool_san.so"
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-fPIC", "-shared", "-x", "c++",
+                           "-I" + os.path.join(root, "include"), "-o", str(lib),
+                           os.path.join(root, "paper_2602_09578_amd", "csrc", "page_pool.hip")])
+    script = textwrap.dedent(f"""
+        import ctypes, sys
+        import numpy as np
+        sys.path.insert(0, {root!r})
+        from oracle.page_pool_ref import PagePoolRef
+        lib = ctypes.CDLL({str(lib)!r})
+        I32, VP = ctypes.c_int32, ctypes.c_void_p
+        P = ctypes.POINTER(I32)
+        lib.marl_page_pool_create.argtypes = [I32, ctypes.POINTER(VP)]
+        lib.marl_page_pool_destroy.argtypes = [VP]; lib.marl_page_pool_destroy.restype = None
+        lib.marl_page_pool_alloc.argtypes = [VP, I32, P]
+        lib.marl_page_pool_release.argtypes = [VP, P, I32]
+        lib.marl_page_pool_retain.argtypes = [VP, P, I32]
+        lib.marl_page_pool_fork.argtypes = [VP, P, I32, P]
+        lib.marl_page_pool_prepare_append.argtypes = [VP, P, I32, I32, P, P]
+        lib.marl_page_pool_drop.argtypes = [VP, P, I32]
+        lib.marl_page_pool_query.argtypes = [VP, I32, P, P]
+        N, MAXP = 37, 5
+        h = VP(); assert lib.marl_page_pool_create(N, ctypes.byref(h)) == 0
+        ref = PagePoolRef(N)
+        rng = np.random.default_rng(5)
+        rows, lens, rrows = [], [], []
+        ptr = lambda a: a.ctypes.data_as(P)
+        for it in range(3000):
+            op = rng.integers(0, 6)
+            if op == 0 or not rows:
+                n = int(rng.integers(1, 4)); out = np.empty(4, dtype=np.int32)
+                rc = lib.marl_page_pool_alloc(h, n, ptr(out)); rrc, pages = ref.alloc(n)
+                assert rc == rrc
+                if rc == 0:
+                    assert list(out[:n]) == pages
+                    row = np.full(MAXP, -1, dtype=np.int32); row[:n] = out[:n]
+                    rows.append(row); rrows.append(list(pages)); lens.append(16 * (n - 1) + int(rng.integers(1, 17)))
+            elif op == 1:
+                k = int(rng.integers(len(rows))); child = np.full(MAXP, -1, dtype=np.int32)
+                rc = lib.marl_page_pool_fork(h, ptr(rows[k]), lens[k], ptr(child)); rrc, rchild = ref.fork(rrows[k], lens[k])
+                assert rc == rrc == 0 and [int(x) for x in child[:len(rchild)]] == rchild
+                rows.append(child); rrows.append(rchild); lens.append(lens[k])
+            elif op in (2, 3):
+                k = int(rng.integers(len(rows)))
+                if lens[k] < MAXP * 16:
+                    s, d = I32(-1), I32(-1)
+                    rc = lib.marl_page_pool_prepare_append(h, ptr(rows[k]), MAXP, lens[k], ctypes.byref(s), ctypes.byref(d))
+                    assert (rc, s.value, d.value) == ref.prepare_append(rrows[k], MAXP, lens[k])
+                    if rc == 0:
+                        lens[k] += 1
+            elif op == 4:
+                k = int(rng.integers(len(rows)))
+                assert lib.marl_page_pool_drop(h, ptr(rows[k]), lens[k]) == ref.drop(rrows[k], lens[k]) == 0
+                rows.pop(k); rrows.pop(k); lens.pop(k)
+            else:                                   # invalid calls must change nothing
+                bad = np.array([int(rng.integers(0, N)), int(rng.choice([-1, N, N + 2])), int(rng.integers(0, N))], dtype=np.int32)
+                assert lib.marl_page_pool_release(h, ptr(bad), 3) == ref.release([int(x) for x in bad]) == -1
+                assert lib.marl_page_pool_retain(h, ptr(bad), 3) == ref.retain([int(x) for x in bad]) == -1
+        for p in range(N):
+            c = I32(0); assert lib.marl_page_pool_query(h, p, ctypes.byref(c), None) == 0
+            assert c.value == ref.count[p], (p, c.value, ref.count[p])
+        lib.marl_page_pool_destroy(h)
+        print("clean")
+    """)
+    asan = subprocess.check_output(["g++", "-print-file-name=libasan.so"], text=True).strip()
+    env = dict(os.environ, LD_PRELOAD=(os.environ.get("LD_PRELOAD", "") + " " + asan).strip(), ASAN_OPTIONS="detect_leaks=0")   # the interpreter itself leaks at exit
+    r = subprocess.run([sys.executable, "-c", script], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0 and "clean" in r.stdout, r.stdout[-3000:]
