@@ -9,6 +9,7 @@ Prints ONE JSON line.  The CPU baseline leg times the float64 checker on a bound
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -27,22 +28,30 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes one suffix_kernel launch moves on this workload, from hardware counters
 # (profiles/decode_step_qwen7b_hbm_counters.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
-# factors a copy kernel of known size gives).  Valid only for the kernel source it was taken
-# with: reported as null when the source has changed since.
+# factors a copy kernel of known size gives).  Valid only for the kernel source and flags it was taken
+# with: reported as null when either has changed since.
 SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5527.2e6 + 29.0e6,
-                  "kernel_sources_sha256": "ef5f0bb71015b1cb9ea21cb02a523a922226a7660a3a9a8232d5bf52926cc68d"}
-SUFFIX_SOURCES = ("csrc/attn_kernels.hip", "csrc/wave_ops.h", "build.py")   # sources and compiler flags
+                  "kernel_sources_sha256": "b8c81e414f842854d54bd04cf9d990370be8f036c4313bdc259a1eb72b31afb9"}
+SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
+
+
+def suffix_kernel_hash():
+    """Hash of what the suffix kernel is built from: its sources and its compiler flags (include paths aside)."""
+    from paper_2602_09578_amd.build import FLAGS, FILE_FLAGS
+    h = hashlib.sha256()
+    for name in SUFFIX_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2602_09578_amd", "csrc", name), "rb").read())
+    h.update(" ".join(f for f in FLAGS + FILE_FLAGS.get("attn_kernels.hip", []) if not f.startswith("-I")).encode())
+    return h.hexdigest()
 
 
 def suffix_traffic(workload: str):
-    import hashlib
-    h = hashlib.sha256()
+    """Counter-measured HBM bytes per suffix_kernel launch, or None when they do not apply."""
     try:
-        for name in SUFFIX_SOURCES:
-            h.update(open(os.path.join(ROOT, "paper_2602_09578_amd", name), "rb").read())
+        digest = suffix_kernel_hash()
     except OSError:
         return None
-    if workload != SUFFIX_TRAFFIC["workload"] or h.hexdigest() != SUFFIX_TRAFFIC["kernel_sources_sha256"]:
+    if workload != SUFFIX_TRAFFIC["workload"] or digest != SUFFIX_TRAFFIC["kernel_sources_sha256"]:
         return None
     return SUFFIX_TRAFFIC["bytes"]
 
