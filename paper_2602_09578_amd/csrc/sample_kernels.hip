@@ -41,16 +41,53 @@ __device__ __forceinline__ void load8(const uint16_t* x, long pos, long end, flo
   }
 }
 
-__device__ __forceinline__ float wave_max(float v) {
+// the 8 logits at x[pos .. pos+8) as four packed words (token 2d in the low half of word d);
+// positions past the end read as -inf
+__device__ __forceinline__ u32x4 load8_words(const uint16_t* x, long pos, long end) {
+  const uint16_t* p = x + pos;
+  if (pos + 8 <= end && (reinterpret_cast<uintptr_t>(p) & 15) == 0)
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  u32x4 v;
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d));
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t lo = pos + 2 * d < end ? p[2 * d] : 0xff80u;
+    const uint32_t hi = pos + 2 * d + 1 < end ? p[2 * d + 1] : 0xff80u;
+    v[d] = lo | (hi << 16);
+  }
   return v;
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  return v;
+
+// Reductions over the 64 lanes, result in every lane, inside the vector ALU: four DPP steps
+// all-reduce each row of 16 lanes (swap neighbours, swap pairs, mirror the halves of 8, mirror
+// the row), two row swaps combine the four rows.  (A shuffle-based reduction keeps six
+// lane-address registers alive and goes through the LDS crossbar six times per call, each a
+// dependent round trip.)
+template <class T, class Op>
+__device__ __forceinline__ T wave_allreduce(T v, Op op) {
+  static_assert(sizeof(T) == 4, "32-bit values");
+  auto dpp = [](T x, auto ctrl_tag) {
+    constexpr int ctrl = decltype(ctrl_tag)::value;
+    return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xf, 0xf, false));
+  };
+  v = op(v, dpp(v, std::integral_constant<int, 0xB1>{}));    // quad_perm [1, 0, 3, 2]
+  v = op(v, dpp(v, std::integral_constant<int, 0x4E>{}));    // quad_perm [2, 3, 0, 1]
+  v = op(v, dpp(v, std::integral_constant<int, 0x141>{}));   // row_half_mirror
+  v = op(v, dpp(v, std::integral_constant<int, 0x140>{}));   // row_mirror
+  // (the swap results are copied to scalars first: a bit cast applied directly to an element of
+  // the returned vector reads element 0 for both)
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const uint32_t a0 = a[0], a1 = a[1];
+  v = op(__builtin_bit_cast(T, a0), __builtin_bit_cast(T, a1));
+  const uint32_t w = __builtin_bit_cast(uint32_t, v);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  const uint32_t b0 = b[0], b1 = b[1];
+  return op(__builtin_bit_cast(T, b0), __builtin_bit_cast(T, b1));
 }
+template <class T>
+__device__ __forceinline__ T wave_allreduce_sum(T v) { return wave_allreduce(v, [](T x, T y) { return x + y; }); }
+__device__ __forceinline__ float wave_max(float v) { return wave_allreduce(v, [](float x, float y) { return fmaxf(x, y); }); }
+__device__ __forceinline__ float wave_sum(float v) { return wave_allreduce_sum(v); }
 __device__ __forceinline__ float wave_inclusive_scan(float v, int lane) {
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -68,27 +105,41 @@ __global__ __launch_bounds__(256) void sample_scan_kernel(SampleArgs a) {
   const int first = (blockIdx.x % a.groups_per_row) * 4 * a.chunks_per_wave;
   const uint16_t* x = a.logits + (size_t)row * a.vocab;
   const float c = a.inv_temp_log2e;
+  // the words of the wave's next chunk are requested before the current chunk is reduced
+  u32x4 cur[kIters], nxt[kIters];
+  auto fetch = [&](int chunk, u32x4 (&w)[kIters]) {
+    const long base = (long)chunk * kChunk;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) w[it] = load8_words(x, base + it * 512 + lane * 8, a.vocab);
+  };
+  if (first + wave < a.num_chunks) fetch(first + wave, cur);
   for (int k = 0; k < a.chunks_per_wave; ++k) {
     const int chunk = first + wave + 4 * k;
     if (chunk >= a.num_chunks) break;
-    const long base = (long)chunk * kChunk;
-    float y[kIters][8];
-#pragma unroll
-    for (int it = 0; it < kIters; ++it) load8(x, base + it * 512 + lane * 8, a.vocab, c, y[it]);
+    const bool more = k + 1 < a.chunks_per_wave && chunk + 4 < a.num_chunks;   // wave-uniform
+    if (more) fetch(chunk + 4, nxt);
     float m = -INFINITY;
 #pragma unroll
     for (int it = 0; it < kIters; ++it)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) m = fmaxf(m, y[it][e]);
-    m = wave_max(m);
+      for (int d = 0; d < 4; ++d)
+        m = fmaxf(m, fmaxf(__uint_as_float(cur[it][d] << 16), __uint_as_float(cur[it][d] & 0xffff0000u)));
+    m = wave_max(m) * c;                 // c > 0: the scaled maximum is the maximum of the scaled values
     const float ms = m == -INFINITY ? 0.f : m;
     float s = 0.f;
 #pragma unroll
     for (int it = 0; it < kIters; ++it)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += ex2(y[it][e] - ms);
+      for (int d = 0; d < 4; ++d) {
+        s += ex2(__builtin_fmaf(__uint_as_float(cur[it][d] << 16), c, -ms));
+        s += ex2(__builtin_fmaf(__uint_as_float(cur[it][d] & 0xffff0000u), c, -ms));
+      }
     s = wave_sum(s);
     if (lane == 0) a.partials[(size_t)row * a.num_chunks + chunk] = make_float2(m, s);
+    if (more) {
+#pragma unroll
+      for (int it = 0; it < kIters; ++it) cur[it] = nxt[it];
+    }
   }
 }
 
@@ -227,20 +278,6 @@ __device__ __forceinline__ float value_of_key(int key) {
   return __uint_as_float(bits << 16);
 }
 
-// the 8 logits at x[pos .. pos+8) as four packed words; positions past the end read as -inf
-__device__ __forceinline__ u32x4 load8_words(const uint16_t* x, long pos, long end) {
-  const uint16_t* p = x + pos;
-  if (pos + 8 <= end && (reinterpret_cast<uintptr_t>(p) & 15) == 0) return *reinterpret_cast<const u32x4*>(p);
-  u32x4 v;
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    const uint32_t lo = pos + 2 * d < end ? p[2 * d] : 0xff80u;
-    const uint32_t hi = pos + 2 * d + 1 < end ? p[2 * d + 1] : 0xff80u;
-    v[d] = lo | (hi << 16);
-  }
-  return v;
-}
-
 struct TpShared {
   uint32_t hist[kWin];          // pass 2: counts; pass 3: per-(tile, wave) sums (reused)
   double wave_d[kTpWaves];
@@ -329,33 +366,6 @@ __device__ __forceinline__ void sweep_row(const uint16_t* x, long V, int tid, F&
 // the two bf16 of a word widened to float
 __device__ __forceinline__ float lo_val(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_val(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// Sum over the 64 lanes, result in every lane, inside the vector ALU: four DPP steps all-reduce
-// each row of 16 lanes (swap neighbours, swap pairs, mirror the halves of 8, mirror the row),
-// two row swaps combine the four rows.  (A shuffle-based reduction keeps six lane-address
-// registers alive and goes through the LDS crossbar twelve times per call.)
-template <class T>
-__device__ __forceinline__ T wave_allreduce_sum(T v) {
-  static_assert(sizeof(T) == 4, "32-bit values");
-  auto dpp = [](T x, auto ctrl_tag) {
-    constexpr int ctrl = decltype(ctrl_tag)::value;
-    return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xf, 0xf, false));
-  };
-  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1, 0, 3, 2]
-  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2, 3, 0, 1]
-  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
-  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
-  // (the swap results are copied to scalars first: a bit cast applied directly to an element of
-  // the returned vector reads element 0 for both)
-  const uint32_t u = __builtin_bit_cast(uint32_t, v);
-  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const uint32_t a0 = a[0], a1 = a[1];
-  v = __builtin_bit_cast(T, a0) + __builtin_bit_cast(T, a1);
-  const uint32_t w = __builtin_bit_cast(uint32_t, v);
-  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-  const uint32_t b0 = b[0], b1 = b[1];
-  return __builtin_bit_cast(T, b0) + __builtin_bit_cast(T, b1);
-}
 
 // a value that is the same in every lane, moved to a scalar register (frees a vector register)
 __device__ __forceinline__ float uniform_f(float v) { return __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(v))); }
