@@ -64,7 +64,9 @@ def check(logits: torch.Tensor, u: np.ndarray, T: float, top_p: float, rows_to_c
     (7, 4099, 1.0, 0.99), (5, 7, 1.0, 0.6), (2, 1, 1.0, 0.3), (9, 20481, 0.9, 0.1), (6, 8192, 1.0, 1.0),
     (6, 8193, 1.3, 1e-4),
     # rows longer than the register-resident variant holds (163840 logits): every pass re-reads memory
-    (3, 200003, 1.0, 0.9), (2, 262144, 0.7, 0.97)])
+    (3, 200003, 1.0, 0.9), (2, 262144, 0.7, 0.97),
+    # the two sides of that limit
+    (2, 163840, 1.0, 0.8), (2, 163841, 1.0, 0.8)])
 def test_tokens_match_the_reference(rows, vocab, T, top_p):
     print("case: top-p", rows, vocab, T, top_p, flush=True)
     lp = I.build_logprob_inputs(rows, vocab, 3.0, 31, temperature=T)
