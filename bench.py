@@ -135,6 +135,24 @@ def main():
     assert B.marl_attn_read_flags(call.workspace) == 0
     assert torch.isfinite(lp_out).all().item() and torch.isfinite(call.out.float()).all().item()
 
+    # the same step captured once into a HIP graph and replayed K times (the entry points only
+    # enqueue kernels, so they can be captured): what a launch-bound decode loop would run
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(a.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_per_step_graph = (time.perf_counter() - t2) / a.steps * 1e3
+    del graph
+
     ms_per_step = dt / a.steps * 1e3
     ptok, stok = attn.unique_kv_tokens()
     bpt = attn.kv_bytes_per_token()
@@ -160,6 +178,7 @@ def main():
                    "suffix_chunk_tokens": call.layout.suffix_chunk_tokens,
                    "prefix_chunk_tokens": call.layout.prefix_chunk_tokens},
         "stage_ms": stage_ms,
+        "ms_per_step_graph_replay": ms_per_step_graph,
         "ms_per_step_with_stage_events": dt_prof / a.steps * 1e3,
         "attn_unique_kv_GBps": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9,
         "attn_pct_of_hbm_peak": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS * 100,
