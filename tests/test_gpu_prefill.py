@@ -61,6 +61,17 @@ def test_chunked_prefill_with_context():
     check(I.build_prefill_inputs(8, 2, [40, 7, 64, 1, 130], [5, 16, 96, 300, 257], seed=4), B.MARL_OUT_BF16)
 
 
+@pytest.mark.parametrize("scale", [1.0, -0.7, 0.0])
+def test_peaked_flat_and_sign_flipped_scores(scale):
+    # scale 1 makes the scores ~N(0, 128): nearly one-hot rows whose running maximum keeps moving
+    # (the accumulator rescale runs in most steps); a negative scale flips every score; scale 0
+    # gives uniform weights (running means of the values)
+    from dataclasses import replace
+    inp = I.build_prefill_inputs(28, 4, [300, 77, 513], [0, 64, 5], seed=21)
+    check(replace(inp, scale=scale))
+    check(replace(inp, scale=scale), B.MARL_OUT_BF16)
+
+
 def test_many_small_groups_and_more_than_one_plan_round():
     rng = np.random.default_rng(0)
     lens = rng.integers(0, 12, size=1500).tolist()      # plan scans 1024 groups per round
