@@ -110,6 +110,17 @@ def test_negative_and_zero_scale():
         check_attn(inp, B.MARL_OUT_F32)
 
 
+def test_peaked_scores():
+    # scale 1 makes the scores ~N(0, 128): nearly one-hot weights, a running maximum that keeps moving
+    # (accumulator rescales in most steps), partials whose maxima differ widely at the merge
+    print("case: peaked scores", flush=True)
+    # the outputs are single value rows here (|out| up to ~4, not the ~0.1 of a mean over hundreds of
+    # tokens), so the rounding of a weight to bf16 (2^-9 relative) shows in full: bound 4 * 2^-8
+    inp = custom_inputs([300, 40], [700, 33, 129, 5], [0, 0, 1, 1], 28, 4, seed=12, scale=1.0)
+    check_attn(inp, B.MARL_OUT_F32, tol=4 * 2.0 ** -8)
+    check_attn(inp, B.MARL_OUT_F32, tol=4 * 2.0 ** -8, suffix_chunk_tokens=256, prefix_chunk_tokens=256)
+
+
 def test_reruns_and_page_permutations_are_bit_identical():
     print("case: determinism", flush=True)
     w = I.WORKLOADS["qwen7b"].scaled(32, 8)
