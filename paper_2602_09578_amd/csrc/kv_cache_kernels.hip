@@ -10,10 +10,12 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// One workgroup of 128 threads per (sequence, KV head): thread c stores V channel c (2 bytes,
-// the layout keeps a channel's 16 slots together), threads 0..15 store the key row (16 bytes each).
+// One workgroup of 128 threads per sequence, looping over the KV heads: thread c stores V channel
+// c (2 bytes, the layout keeps a channel's 16 slots together), threads 0..15 store the key row
+// (16 bytes each).  Every thread reads the old length before the barrier; thread 0 stores the
+// new one after it.
 __global__ __launch_bounds__(kD) void kv_append_kernel(KvAppendArgs a) {
-  const int s = blockIdx.x / a.Hkv, kvh = blockIdx.x % a.Hkv;
+  const int s = blockIdx.x;
   const int c = threadIdx.x;
   const int pos = a.suffix_lens[s];
   int flag = 0;
@@ -25,27 +27,19 @@ __global__ __launch_bounds__(kD) void kv_append_kernel(KvAppendArgs a) {
   }
   if (page >= 0) {
     const int slot = pos & (kPage - 1);
-    const size_t blk = ((size_t)page * a.Hkv + kvh) * (kPage * kD);              // elements
-    const uint16_t* kn = a.k_new + ((size_t)s * a.Hkv + kvh) * kD;
-    const uint16_t* vn = a.v_new + ((size_t)s * a.Hkv + kvh) * kD;
-    a.v_pages[blk + (size_t)c * kPage + slot] = vn[c];
-    if (c < 16)
-      *reinterpret_cast<u32x4*>(a.k_pages + blk + (size_t)slot * kD + c * 8) =
-          *reinterpret_cast<const u32x4*>(kn + c * 8);
+    for (int kvh = 0; kvh < a.Hkv; ++kvh) {
+      const size_t blk = ((size_t)page * a.Hkv + kvh) * (kPage * kD);            // elements
+      const uint16_t* kn = a.k_new + ((size_t)s * a.Hkv + kvh) * kD;
+      const uint16_t* vn = a.v_new + ((size_t)s * a.Hkv + kvh) * kD;
+      a.v_pages[blk + (size_t)c * kPage + slot] = vn[c];
+      if (c < 16)
+        *reinterpret_cast<u32x4*>(a.k_pages + blk + (size_t)slot * kD + c * 8) =
+            *reinterpret_cast<const u32x4*>(kn + c * 8);
+    }
   }
   if (flag && c == 0 && a.flags) atomicOr(a.flags, flag);
-}
-
-// lens are bumped by a second tiny kernel so that every (sequence, head) workgroup above
-// reads the same old length
-__global__ void kv_append_bump_kernel(KvAppendArgs a) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= a.NS) return;
-  const int pos = a.suffix_lens[s];
-  if (pos < 0 || pos >= a.max_sp * kPage) return;
-  const int page = a.suffix_table[(size_t)s * a.max_sp + (pos >> 4)];
-  if ((unsigned)page >= (unsigned)a.num_pages) return;
-  a.suffix_lens[s] = pos + 1;
+  __syncthreads();
+  if (page >= 0 && c == 0) a.suffix_lens[s] = pos + 1;
 }
 
 // dst[i] <- src[i] for whole pages (all KV heads, K and V): one workgroup per (pair, K|V)
@@ -68,10 +62,7 @@ __global__ __launch_bounds__(256) void kv_copy_pages_kernel(KvCopyArgs a) {
 
 hipError_t launch_kv_append(const KvAppendArgs& a, hipStream_t st) {
   if (a.NS == 0) return hipSuccess;
-  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)a.NS * a.Hkv), dim3(kD), 0, st, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kv_append_bump_kernel, dim3((a.NS + 255) / 256), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)a.NS), dim3(kD), 0, st, a);
   return hipGetLastError();
 }
 
