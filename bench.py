@@ -122,6 +122,14 @@ def main():
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # the same K steps once more, each bracketed by its own pair of events: median and minimum
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     # timed region 2: the same K steps with the library recording HIP events around every
     # kernel on the call's stream -> per-kernel durations (the events cost a few us per kernel)
     B.marl_profile_begin(a.steps)
@@ -178,6 +186,7 @@ def main():
                    "suffix_chunk_tokens": call.layout.suffix_chunk_tokens,
                    "prefix_chunk_tokens": call.layout.prefix_chunk_tokens},
         "stage_ms": stage_ms,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "ms_per_step_graph_replay": ms_per_step_graph,
         "ms_per_step_with_stage_events": dt_prof / a.steps * 1e3,
         "attn_unique_kv_GBps": (ptok + stok) * bpt / (attn_ms * 1e-3) / 1e9,
