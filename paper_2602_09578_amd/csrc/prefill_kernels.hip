@@ -45,12 +45,8 @@ constexpr int kPfThreads = 64 * kNW;
 constexpr int kPfStepBytes = 2 * kBlockTok * kD * 2;   // K + V of one 32-token step
 constexpr int kPlanThreadsPf = 1024;
 
-#ifndef MARL_PREFILL_DIRECT
-#define MARL_PREFILL_DIRECT 1
-#endif
-// LDS step buffers: 3 with register staging; 4 with direct global-to-LDS loads (two workgroups
-// of 64 KB per CU)
-constexpr int kPfStages = MARL_PREFILL_DIRECT ? 4 : 3;
+// LDS step buffers, filled by direct global-to-LDS loads (two workgroups of 64 KB per CU)
+constexpr int kPfStages = 4;
 struct PrefillLds {
   __attribute__((aligned(16))) char buf[kPfStages][kPfStepBytes];
 };
@@ -213,8 +209,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   // rows of 256 B with the 16-byte chunk index XOR-ed with a key of the row, V as
   // [page][channel][2 halves of 8 slots] with the unit index XOR-ed with (unit >> 3) & 1, so
   // that the 8 lanes of one operand read hit 8 different bank groups.
-#if MARL_PREFILL_DIRECT
-  // Direct variant: global_load_lds_dwordx4 moves the vectors from global memory straight into
+  // global_load_lds_dwordx4 moves the vectors from global memory straight into
   // LDS (the 64 lanes of a wave fill 1 KB in lane order, no registers in between).  Wave `wave`
   // fills, for k < kLoads, the 64 slots from slot w0 of region k * kNW/4 + wave/4; the XOR
   // swizzle (an involution inside a key row / a pair of value units) is applied on the source
@@ -244,32 +239,6 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
           16, 0, 0);
     }
   };
-#else
-  static_assert(kNW % 4 == 0, "a wave's 64 vectors must lie in one 256-vector region");
-  const int w = tid & 255;
-  const uint32_t lane_off = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)w * 16;
-  int region[kLoads], lds_off[kLoads];
-#pragma unroll
-  for (int k = 0; k < kLoads; ++k) {
-    region[k] = k * (kNW / 4) + (wave >> 2);      // = (tid + k * threads) >> 8, wave-uniform
-    const bool is_v = region[k] >> 1;
-    const int slot = w >> 4;
-    lds_off[k] = is_v ? 2 * kBlockTok * kD + (region[k] & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
-                      : ((region[k] & 1) * 16 + slot) * 256 + (((w & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)) << 4);
-  }
-  auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
-#pragma unroll
-    for (int k = 0; k < kLoads; ++k) {
-      const char* base = reinterpret_cast<const char*>((region[k] >> 1) ? a.v_pages : a.k_pages) +
-                         (size_t)((region[k] & 1) ? p1 : p0) * page_bytes;
-      st[k] = *reinterpret_cast<const u32x4*>(base + lane_off);
-    }
-  };
-  auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
-#pragma unroll
-    for (int k = 0; k < kLoads; ++k) *reinterpret_cast<u32x4*>(buf + lds_off[k]) = st[k];
-  };
-#endif
   const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
   const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
 
@@ -411,7 +380,6 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
     }
   };
 
-#if MARL_PREFILL_DIRECT
   // ring of kPfStages LDS buffers: per iteration wait until this wave's part of step n has landed
   // (all but the youngest kPfStages-2 steps' loads), a bare workgroup barrier (everybody's part
   // has landed and everybody has finished reading buffer (n-1) % kPfStages; a fence would wait
@@ -445,42 +413,6 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   for (; n < nsteps; ++n) ring_step(n, compute_edge);
   __builtin_amdgcn_s_waitcnt(pf_vmcnt_imm(0));
   __syncthreads();
-#else
-  // three register stages and three LDS buffers, as in the decode prefix kernel
-  u32x4 st0[kLoads], st1[kLoads], st2[kLoads];
-  int p0, p1;
-  load_ids(0, p0, p1);
-  issue(p0, p1, st0);
-  load_ids(1, p0, p1);
-  issue(p0, p1, st1);
-  load_ids(2, p0, p1);
-  issue(p0, p1, st2);
-  load_ids(3, p0, p1);
-  stage_to_lds(st0, lds.buf[0]);
-  __syncthreads();
-  for (int n = 0; n < nsteps; n += 3) {
-    issue(p0, p1, st0);
-    load_ids(n + 4, p0, p1);
-    compute(n, lds.buf[0]);
-    stage_to_lds(st1, lds.buf[1]);
-    __syncthreads();
-    if (n + 1 < nsteps) {
-      issue(p0, p1, st1);
-      load_ids(n + 5, p0, p1);
-      compute_edge(n + 1, lds.buf[1]);
-      stage_to_lds(st2, lds.buf[2]);
-      __syncthreads();
-    }
-    if (n + 2 < nsteps) {
-      issue(p0, p1, st2);
-      load_ids(n + 6, p0, p1);
-      compute_edge(n + 2, lds.buf[2]);
-      stage_to_lds(st0, lds.buf[0]);
-      __syncthreads();
-    }
-  }
-
-#endif
   // lane (i, j) holds channels 16*ct + 4*j .. +3 of q-row i
 #pragma unroll
   for (int qt = 0; qt < kMT; ++qt) {
