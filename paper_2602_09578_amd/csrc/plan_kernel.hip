@@ -33,6 +33,12 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
   return v;
 }
 
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d);
+  return v;
+}
+
 // out[i] = sum of in[0..i) for i < n (in and out may alias); returns the total to every
 // thread.  tmp: 17 shared ints.  Must be called by all 1024 threads.  GLOBAL_IN: `in` is
 // global memory written earlier in this kernel.
@@ -84,6 +90,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   __syncthreads();
 
   // sequences: rank inside the group, histogram of suffix items by cost class
+  // (full chunks and long items: counted per thread, added once per wave, since same-address LDS
+  // atomics run one lane at a time)
+  int nfull_mine = 0, nlong_mine = 0;
   for (int s = tid; s < a.NS; s += kPlanThreads) {
     const int g = a.group_of_seq[s];
     int rank = -1;
@@ -92,10 +101,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
     a.seq_rank[s] = rank;
     const int S = clamp_len(a.suffix_lens[s], max_st, flags);
     const int nfull = S / Cs, tail = S % Cs;
-    if (nfull) atomicAdd(&hist_s[0], nfull);
+    nfull_mine += nfull;
     if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
-    const int nlong = (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
-    if (nlong) atomicAdd(&n_long_items, nlong);
+    nlong_mine += (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
+  }
+  nfull_mine = wave_sum(nfull_mine);
+  nlong_mine = wave_sum(nlong_mine);
+  if (lane_id() == 0) {
+    if (nfull_mine) atomicAdd(&hist_s[0], nfull_mine);
+    if (nlong_mine) atomicAdd(&n_long_items, nlong_mine);
   }
   __threadfence();
   __syncthreads();
@@ -211,6 +225,9 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
   __shared__ int hist_p[kSmallMaxClasses];
   __shared__ int tmp[17];
   __shared__ int n_long_items;
+  // clamped prefix lengths, where there is room for them (else they are re-read from global memory)
+  constexpr bool kPrefixLensInLds = kSmallMaxGroups <= 2048;
+  __shared__ int prefix_len[kPrefixLensInLds ? kSmallMaxGroups : 1];
   const int tid = threadIdx.x;
   const int Cs = a.Cs, Cp = a.Cp, R = a.R, QB = a.qblock_rows;
   const int ncls_s = Cs / 32, ncls_p = Cp / 32;
@@ -249,6 +266,9 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
   if (tid < 64) a.counters[tid] = 0;
   __syncthreads();
 
+  // full chunks and long items are counted per thread and added once per wave: nearly every
+  // sequence contributes to these two words, and same-address LDS atomics run one lane at a time
+  int nfull_mine = 0, nlong_mine = 0;
 #pragma unroll
   for (int k = 0; k < kSeqsPerThread; ++k) {
     const int s = tid + k * kPlanThreads;
@@ -261,11 +281,16 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
       if constexpr (kKeep) S = S_keep[k] = clamp_len(S_keep[k], max_st, flags);
       else S = clamp_len(a.suffix_lens[s], max_st, flags);
       const int nfull = S / Cs, tail = S % Cs;
-      if (nfull) atomicAdd(&hist_s[0], nfull);
+      nfull_mine += nfull;
       if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
-      const int nlong = (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
-      if (nlong) atomicAdd(&n_long_items, nlong);
+      nlong_mine += (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
     }
+  }
+  nfull_mine = wave_sum(nfull_mine);
+  nlong_mine = wave_sum(nlong_mine);
+  if (lane_id() == 0) {
+    if (nfull_mine) atomicAdd(&hist_s[0], nfull_mine);
+    if (nlong_mine) atomicAdd(&n_long_items, nlong_mine);
   }
   __syncthreads();
   const int nseq_grouped = block_exclusive_scan<false>(cnt, start, a.NG, tmp);
@@ -276,6 +301,7 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
     const int g = tid + k * kPlanThreads;
     if (g < a.NG) {
       P_of[k] = clamp_len(P_of[k], max_pt, flags);
+      if constexpr (kPrefixLensInLds) prefix_len[g] = P_of[k];
       const int nqb = (cnt[g] * R + QB - 1) / QB;
       const int nfull = P_of[k] / Cp, tail = P_of[k] % Cp;
       if (nqb) {
@@ -295,8 +321,12 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
       const int g = G(k);
       if (rank_of[k] >= 0) members[start[g] + rank_of[k]] = (MemberId)s;
       const int S = S_len(k);
-      int dummy = 0;
-      const int P = rank_of[k] >= 0 ? clamp_len(a.prefix_lens[g], max_pt, dummy) : 0;
+      int P = 0;
+      if (rank_of[k] >= 0) {
+        int dummy = 0;
+        if constexpr (kPrefixLensInLds) P = prefix_len[g];
+        else P = clamp_len(a.prefix_lens[g], max_pt, dummy);
+      }
       a.seq_chunks[s] = ((P + Cp - 1) / Cp) | (((S + Cs - 1) / Cs) << 16);
       const int nfull = S / Cs, tail = S % Cs;
       if (nfull) {

@@ -65,6 +65,21 @@ def test_plan_matches_reference(name, pdiv, ldiv):
     compare(shape, L.prefix_lens, L.suffix_lens, L.group_of_seq, w.Hq, w.Hkv)
 
 
+@pytest.mark.parametrize("NS,S", [(2048, 40), (1000, 200), (333, 300), (64 * 9 + 1, 0)])
+def test_plan_equal_lengths(NS, S):
+    """Every sequence at the same decode step: one cost class (or none) takes every item."""
+    print("case: plan equal lengths", NS, S, flush=True)
+    G = 8
+    NG = -(-NS // G)
+    gos = (np.arange(NS) // G).astype(np.int32)
+    pl = np.full(NG, 700, np.int32)
+    sl = np.full(NS, S, np.int32)
+    sl[NS // 2] = S + 64          # but for one sequence
+    shape = B.make_shape(NS, NG, 28, 4, 10, 44, 32, suffix_chunk_tokens=256)
+    got = compare(shape, pl, sl, gos, 28, 4)
+    assert len({tuple(it) for it in got["sitems"].tolist()}) == len(got["sitems"])   # no place given twice
+
+
 def test_plan_shuffled_groups_small_chunks_and_bad_values():
     print("case: plan shuffled", flush=True)
     rng = np.random.default_rng(3)
