@@ -76,7 +76,7 @@ def cpu_baseline(attn_dev: I.AttnInputs, lp_dev: I.LogprobInputs, seq_stride: in
     t_lp = time.perf_counter() - t0
     per_seq = t_attn / len(pick) + t_lp / rows      # one sequence's attention + its log-prob row
     return {"value": 1.0 / per_seq, "unit": "sequences*steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"every {seq_stride}th sequence ({len(pick)} of {attn_dev.num_seqs}) for attention "
+            "sample": f"every sequence with index divisible by {seq_stride} ({len(pick)} of {attn_dev.num_seqs}) for attention "
                       f"({t_attn:.2f} s) and {rows} of {lp_dev.logits.shape[0]} logit rows ({t_lp:.2f} s)",
             "attn_seqs_per_s": len(pick) / t_attn, "logprob_rows_per_s": rows / t_lp}
 
