@@ -133,6 +133,8 @@ int marl_workspace_bytes(const marl_attn_shape* shape, size_t* bytes);
  *   out                 bf16 or float32 [NS, Hq, 128] per shape->out_dtype
  *   workspace           at least marl_workspace_bytes() bytes, 256-byte aligned; contents on
  *                       entry are irrelevant, contents on exit are the work list and partials
+ * q, k_pages, v_pages and out must be 16-byte aligned (MARL_INVALID_ARG otherwise): they are
+ * accessed as 16-byte vectors.
  * Unused slots of a partly filled page and pages no table names are never read into a result.
  * Calls that share a workspace must be ordered on one stream.
  *
@@ -171,7 +173,8 @@ int marl_attn_read_flags(const void* workspace, int32_t* flags_host, void* strea
  * NULL, MARL_FLAG_LEN_CLAMPED / MARL_FLAG_BAD_PAGE is OR-ed into *flags (device int32).
  * Only num_seqs, num_kv_heads, head_dim, page_size, num_pages and max_suffix_pages of the
  * shape are used.  Device arrays: k_new, v_new bf16 [NS, Hkv, 128]; the rest as in
- * marl_decode_attn (k_pages, v_pages and suffix_lens are written).
+ * marl_decode_attn (k_pages, v_pages and suffix_lens are written).  k_new, v_new, k_pages and
+ * v_pages must be 16-byte aligned (MARL_INVALID_ARG otherwise).
  *
  * marl_kv_copy_pages: for i < n copies physical page src[i] to page dst[i] (all KV heads, K
  * and V), the device half of forking a sample from another one (the host allocates dst and

@@ -19,6 +19,8 @@ int hip_fail(hipError_t e, const char* what) {
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// device arrays that the kernels read and write as 16-byte vectors
+bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
 int check_shape(const marl_attn_shape* s) {
@@ -237,6 +239,7 @@ int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t works
   if (a.NS > 0 && (!q || !out || !suffix_lens || !group_of_seq || !k_pages || !v_pages)) return MARL_INVALID_ARG;
   if (a.NS > 0 && a.max_sp > 0 && !suffix_block_table) return MARL_INVALID_ARG;
   if (a.NG > 0 && (!prefix_lens || (a.max_pp > 0 && !prefix_block_table))) return MARL_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)) return MARL_INVALID_ARG;
   if (a.NS == 0) return MARL_OK;
   a.q = static_cast<const uint16_t*>(q);
   a.k_pages = static_cast<const uint16_t*>(k_pages);
@@ -294,6 +297,7 @@ int marl_kv_append(const marl_attn_shape* shape, const void* k_new, const void* 
   if (rc != MARL_OK) return rc;
   if (shape->num_seqs == 0) return MARL_OK;
   if (!k_new || !v_new || !k_pages || !v_pages || !suffix_block_table || !suffix_lens) return MARL_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pages) || !aligned16(v_pages)) return MARL_INVALID_ARG;
   if (shape->max_suffix_pages < 1) return MARL_INVALID_ARG;
   marl::KvAppendArgs a;
   a.k_new = static_cast<const uint16_t*>(k_new);
@@ -319,6 +323,7 @@ int marl_kv_copy_pages(const marl_attn_shape* shape, void* k_pages, void* v_page
   if (n < 0 || n >= (1 << 30)) return MARL_INVALID_ARG;
   if (n == 0) return MARL_OK;
   if (!k_pages || !v_pages || !src || !dst) return MARL_INVALID_ARG;
+  if (!aligned16(k_pages) || !aligned16(v_pages)) return MARL_INVALID_ARG;
   marl::KvCopyArgs a;
   a.k_pages = static_cast<uint16_t*>(k_pages);
   a.v_pages = static_cast<uint16_t*>(v_pages);

@@ -79,6 +79,12 @@ def test_decode_attn_argument_errors_without_gpu():
     assert call(ctypes.c_void_p(base + 8), need, p, 1.0) == -1  # misaligned workspace
     assert call(p, need - 1, p, 1.0) == -3                     # too small
     assert call(p, need, None, 1.0) == -1                      # null q
+    assert call(p, need, ctypes.c_void_p(base + 2), 1.0) == -1  # q not 16-byte aligned
+    odd = ctypes.c_void_p(base + 8)
+    for at in range(4):                                        # q, k_pages, v_pages, out in turn
+        args = [p, p, p] + [p] * 5 + [ctypes.c_float(1.0), p]
+        args[[0, 1, 2, 9][at]] = odd
+        assert lib.marl_decode_attn(ctypes.byref(shape), p, need, *args, None) == -1
     assert call(p, need, p, float("nan")) == -1
     assert call(p, need, p, float("inf")) == -1
     assert lib.marl_decode_attn(None, p, need, p, p, p, p, p, p, p, p, ctypes.c_float(1.0), p, None) == -1
@@ -113,6 +119,7 @@ def test_kv_cache_argument_errors_without_gpu():
     p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
     ap = lambda k_new, lens, sh=shape: lib.marl_kv_append(ctypes.byref(sh), k_new, p, p, p, p, lens, None, None)
     assert ap(None, p) == -1 and ap(p, None) == -1
+    assert ap(ctypes.c_void_p(p.value + 4), p) == -1               # k_new not 16-byte aligned
     assert ap(p, p, good_shape(max_suffix_pages=0)) == -1          # no room for any token
     assert ap(p, p, good_shape(head_dim=64)) == -2
     assert ap(p, p, good_shape(num_seqs=0)) == 0                   # nothing to do
