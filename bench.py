@@ -242,9 +242,29 @@ def main():
             tot += ev0.elapsed_time(ev1)
     res["sample_tokens_top_p"] = {"us_per_call": tot / 5 * 1e3, "rows": w.num_seqs, "top_p": 0.9,
                                   "GBps_of_one_read": w.num_seqs * vocab * 2 / (tot / 5 * 1e-3) / 1e9}
+    del s_ws, uniforms
+    # training-side log-probs: one micro-batch of 16 responses x 1024 positions at once (the
+    # same entry point on 8 x the rows: 5 GB of logits)
+    if vocab >= 32768:
+        t_rows = 16 * 1024
+        tl = I.build_logprob_inputs(t_rows, vocab, sigma, w.seed + 1, device=dev)
+        t_need = B.marl_logprobs_workspace_bytes(t_rows, vocab)
+        t_ws = B.alloc_workspace(t_need, dev) if t_need else None
+        t_out = torch.empty(t_rows, dtype=torch.float32, device=dev)
+        tot = 0.0
+        for it in range(7):
+            ev0.record()
+            B.marl_token_logprobs(tl.logits, tl.tokens, tl.temperature, t_out, t_ws)
+            ev1.record()
+            torch.cuda.synchronize()
+            if it >= 2:
+                tot += ev0.elapsed_time(ev1)
+        assert torch.isfinite(t_out).all().item()
+        res["logprobs_training_shape"] = {"ms_per_call": tot / 5, "rows": t_rows,
+                                          "GBps": t_rows * vocab * 2 / (tot / 5 * 1e-3) / 1e9}
+        del tl, t_ws, t_out
     # prompt (prefill) attention over the workload's prompts: the step that creates the shared
     # prefixes; dense causal MFMA work, reported against the bf16 matrix peak
-    del s_ws, uniforms
     pf = I.build_prefill_inputs(w.Hq, w.Hkv, attn.prefix_lens.cpu().tolist(), [0] * w.num_groups, device=dev,
                                 seed=w.seed, poison=False)
     pshape, pws, pout = B.prepare_prefill(pf, B.MARL_OUT_BF16)

@@ -52,6 +52,21 @@ def test_full_size_qwen7b_rows():
     print(check(lp))
 
 
+def test_training_shape_sampled_rows():
+    """A micro-batch of 16 responses x 1024 positions in one call (5 GB of logits): every 37th
+    row, the first and the last against the checker."""
+    print("case: logprobs training shape", flush=True)
+    rows, vocab = 16 * 1024, 152064
+    lp = I.build_logprob_inputs(rows, vocab, 3.0, 29, device="cuda")
+    got = gpu_logprobs(lp)
+    pick = sorted(set(range(0, rows, 37)) | {rows - 1})
+    idx = torch.as_tensor(pick, device="cuda")
+    want = ref.token_logprobs(I.bf16_bits(lp.logits[idx]), lp.tokens[idx].cpu().numpy(), lp.temperature)
+    err = float(np.abs(got[pick] - want).max())
+    assert err <= LOGPROB_TOL, f"max |delta| = {err}"
+    assert np.isfinite(got).all()
+
+
 def test_out_of_range_token_and_masked_logits():
     print("case: logprobs special values", flush=True)
     lp = I.build_logprob_inputs(4, 1000, 3.0, 5)
