@@ -172,7 +172,22 @@ def main():
     Cs = call.layout.suffix_chunk_tokens
     tail = S % Cs
     long_tok = int(((S // Cs) * Cs * (Cs > 128) + tail * (tail > 128)).sum())
-    suffix_gbps = long_tok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
+    if long_tok:
+        suffix_gbps = long_tok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
+        roofline = {"kernel": "suffix_kernel", "bound": "hbm", "achieved": suffix_gbps, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": suffix_traffic(w.name),
+                    "algorithmic_bytes_per_launch": long_tok * bpt, "avg_launch_ms": stage_ms["suffix"]}
+    else:
+        # no item for the suffix kernel (every sequence has at most 128 generated tokens): the prefix
+        # kernel is the dominant one; its QK^T and PV products against the dense bf16 matrix peak
+        flops = 4 * 128 * w.Hq * sum(int(P) * int(n) for P, n in
+                                     zip(attn.prefix_lens.cpu().tolist(),
+                                         np.bincount(attn.group_of_seq.cpu().numpy(), minlength=w.num_groups)))
+        tf = flops / (stage_ms["prefix"] * 1e-3) / 1e12
+        roofline = {"kernel": "prefix_kernel", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+                    "frac": tf / 2500.0, "traffic": None, "algorithmic_flops_per_launch": flops,
+                    "avg_launch_ms": stage_ms["prefix"],
+                    "note": "the launch also processes the short suffix items, which are not in the flops"}
     res = {
         "metric": "rollout decode step throughput (paged shared-prefix decode attention + token log-probs)",
         "value": w.num_seqs / (ms_per_step * 1e-3),
@@ -194,9 +209,7 @@ def main():
         "attn_seq_steps_per_s": w.num_seqs / (attn_ms * 1e-3),
         "logprob_rows_per_s": w.num_seqs / (lp_ms * 1e-3),
         "logprob_GBps": w.num_seqs * vocab * 2 / (lp_ms * 1e-3) / 1e9,
-        "roofline": {"kernel": "suffix_kernel", "bound": "hbm", "achieved": suffix_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": suffix_traffic(w.name),
-                     "algorithmic_bytes_per_launch": long_tok * bpt, "avg_launch_ms": stage_ms["suffix"]},
+        "roofline": roofline,
     }
     # KV append (the cache maintenance that precedes attention in a decode iteration), timed
     # after everything else because it overwrites each sequence's last token

@@ -271,7 +271,9 @@ int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t works
     if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * (a.qblock_rows == marl::kRowsPerQBlockWide ? g_prefix_wide_bpc : g_prefix_bpc), st); })) != hipSuccess)
       return hip_fail(e, "prefix kernel");
   }
-  if (a.max_sp > 0) {
+  // the suffix kernel takes the items of more than kShortTokens tokens: none can exist when
+  // neither a table row nor a chunk holds that many
+  if ((long)a.max_sp * marl::kPage > marl::kShortTokens && a.Cs > marl::kShortTokens) {
     if ((e = T.run(MARL_STAGE_SUFFIX, [&] { return marl::launch_suffix(a, g_num_cus * g_suffix_bpc, st); })) != hipSuccess)
       return hip_fail(e, "suffix kernel");
   }
