@@ -103,6 +103,32 @@ def test_many_groups_use_the_larger_plan_kernels(NG):
     check_attn(inp, B.MARL_OUT_F32)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(seed):
+    """Seeded random shapes: head counts, group sizes (a few of them beyond one query-row block),
+    prefix and generated lengths that mix zeros, page and step boundaries and several chunks,
+    sequences in shuffled order, default and small chunks."""
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    R = int(rng.choice([1, 2, 4, 7, 8, 16]))
+    NG = int(rng.integers(1, 9))
+    sizes = rng.choice([1, 2, 3, 8, 20, 40], size=NG, p=[0.3, 0.2, 0.2, 0.2, 0.05, 0.05])
+    gos = rng.permutation(np.repeat(np.arange(NG), sizes))
+    edge = np.array([0, 1, 15, 16, 17, 31, 32, 33, 127, 128, 129])
+    plens = np.where(rng.random(NG) < 0.4, rng.choice(edge, NG), rng.integers(0, 700, NG))
+    slens = np.where(rng.random(len(gos)) < 0.4, rng.choice(edge, len(gos)), rng.integers(0, 600, len(gos)))
+    print("case: random shape", seed, "Hq", Hkv * R, "Hkv", Hkv, "groups", sizes.tolist(), flush=True)
+    inp = custom_inputs(plens, slens, gos, Hkv * R, Hkv, seed=seed)
+    check_attn(inp, B.MARL_OUT_F32)
+    # bf16 output: a sequence of a few tokens can have |out| > 1, where the half ulp of the final
+    # rounding alone (|out| 2^-8 at most) exceeds the absolute bar, so it is allowed on top
+    want = oracle_attn(inp)
+    got, _ = gpu_attn(inp, B.MARL_OUT_BF16, suffix_chunk_tokens=int(rng.choice([32, 96, 256])),
+                      prefix_chunk_tokens=int(rng.choice([32, 64, 160])))
+    assert np.isfinite(got).all()
+    assert np.all(np.abs(got - want) <= ATTN_TOL + np.abs(want) * 2.0 ** -8)
+
+
 def test_negative_and_zero_scale():
     print("case: scale sign", flush=True)
     for scale in (-0.11, 0.0):
