@@ -55,6 +55,22 @@ def test_ragged_prompts_match_reference(Hq, Hkv, out_dtype):
     check(I.build_prefill_inputs(Hq, Hkv, lens, [0] * len(lens), seed=Hq + Hkv), out_dtype)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(seed):
+    """Seeded random head counts, prompt lengths (zeros, page and row-block boundaries, a few
+    hundred tokens) and context lengths in front of the chunk."""
+    rng = np.random.default_rng(500 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    Rq = int(rng.choice([1, 2, 4, 7, 8, 16]))
+    n = int(rng.integers(1, 7))
+    edge = np.array([0, 1, 15, 16, 17, 47, 48, 49, 191, 192, 193])
+    lens = np.where(rng.random(n) < 0.4, rng.choice(edge, n), rng.integers(1, 420, n))
+    pos0 = np.where(rng.random(n) < 0.5, 0, rng.integers(0, 300, n))
+    print("case: prefill random shape", seed, Hkv * Rq, Hkv, lens.tolist(), pos0.tolist(), flush=True)
+    out_dtype = B.MARL_OUT_F32 if seed % 2 == 0 else B.MARL_OUT_BF16
+    check(I.build_prefill_inputs(Hkv * Rq, Hkv, lens.tolist(), pos0.tolist(), seed=seed), out_dtype)
+
+
 def test_chunked_prefill_with_context():
     # chunks that start in the middle of a page, at a page boundary and deep into the prompt
     check(I.build_prefill_inputs(28, 4, [40, 7, 64, 1, 130], [5, 16, 96, 300, 257], seed=3))
