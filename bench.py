@@ -30,8 +30,8 @@ HBM_PEAK_GBPS = 8000.0
 # (profiles/decode_step_qwen7b_hbm_counters.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors a copy kernel of known size gives).  Valid only for the kernel source and flags it was taken
 # with: reported as null when either has changed since.
-SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5527.2e6 + 29.0e6,
-                  "kernel_sources_sha256": "b8c81e414f842854d54bd04cf9d990370be8f036c4313bdc259a1eb72b31afb9"}
+SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5556.9e6 + 14.1e6,
+                  "kernel_sources_sha256": "ace44560691cca4babba1176c5c953f74d7281f67cc85a08472a25b9579b2258"}
 SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 

@@ -51,11 +51,17 @@ struct ItemLds {
 //   NW = 1: called by one wave on its own (no LDS, no barrier): for short items.
 //   row_index[qt]: for this lane's q-row (i) of tile qt, seq*Hq + head, or -1 if the row
 //   does not exist.  slot: partial slot of this chunk.
+//   finish (NW = 4 only, workgroup-uniform): the item holds all of the sequence's own tokens,
+//   so the rows' only other partials are the n_prefix_partials prefix partials of its group,
+//   which an earlier kernel has completed: the workgroup merges them with its own result (the
+//   merge kernel's formula and order: prefix slots first) and writes the final output rows
+//   instead of a partial.
 template <int MT, int NW>
 __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* __restrict__ table_row,
                                              const int tok_begin, const int tok_end, const int kvh,
                                              const int (&row_index)[MT], const int slot,
-                                             ItemLds<MT>& lds, int& bad_page) {
+                                             ItemLds<MT>& lds, int& bad_page,
+                                             const bool finish = false, const int n_prefix_partials = 0) {
   const int lane = threadIdx.x & 63;
   const int wave = NW == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = lane & 15, j = lane >> 4;
@@ -247,9 +253,38 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
           ll += lds.l[w][r] * f;
           o += *reinterpret_cast<const f32x4*>(&lds.acc[w][r][4 * c4]) * f;
         }
-        const size_t ps = (size_t)ridx * nslot + slot;
-        *reinterpret_cast<f32x4*>(a.partial_o + ps * kD + 4 * c4) = o;
-        if (c4 == 0) a.partial_ml[ps] = make_float2(mm, ll);
+        if (!finish) {
+          const size_t ps = (size_t)ridx * nslot + slot;
+          *reinterpret_cast<f32x4*>(a.partial_o + ps * kD + 4 * c4) = o;
+          if (c4 == 0) a.partial_ml[ps] = make_float2(mm, ll);
+        } else {
+          const size_t p0 = (size_t)ridx * nslot;
+          float mstar = mm;
+          for (int k = 0; k < n_prefix_partials; ++k) mstar = fmaxf(mstar, a.partial_ml[p0 + k].x);
+          float denom = 0.f;
+          f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+          for (int k = 0; k < n_prefix_partials; ++k) {
+            const float2 v = a.partial_ml[p0 + k];
+            const f32x4 ok = *reinterpret_cast<const f32x4*>(a.partial_o + (p0 + k) * kD + 4 * c4);
+            const float f = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(v.x - mstar);
+            denom = __builtin_fmaf(v.y, f, denom);
+            sum += ok * f;
+          }
+          {
+            const float f = (mm == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mm - mstar);
+            denom = __builtin_fmaf(ll, f, denom);
+            sum += o * f;
+          }
+          f32x4 res = {0.f, 0.f, 0.f, 0.f};
+          if (denom > 0.f) res = sum * (1.0f / denom);
+          if (a.out_dtype == MARL_OUT_F32) {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + (size_t)ridx * kD + 4 * c4) = res;
+          } else {
+            typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+            const bf16x4 v = {(__bf16)res[0], (__bf16)res[1], (__bf16)res[2], (__bf16)res[3]};
+            *reinterpret_cast<bf16x4*>(reinterpret_cast<uint16_t*>(a.out) + (size_t)ridx * kD + 4 * c4) = v;
+          }
+        }
       }
     }
     // the next use of this LDS comes after the workgroup's next trip to the work queue, which
@@ -317,8 +352,10 @@ void suffix_kernel(AttnArgs a) {
     const int s = it.x;
     const int i = threadIdx.x & 15;
     const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
+    // a sequence whose own tokens are this one item: the output rows are finished here
+    const int chunks = ld_uniform(a.seq_chunks + s);
     process_item<1, kSuffixWaves>(a, a.suffix_table + (size_t)s * a.max_sp, it.y, it.z, kvh, row_index,
-                                  a.NCp + it.y / a.Cs, lds, bad_page);
+                                  a.NCp + it.y / a.Cs, lds, bad_page, (chunks >> 16) == 1, chunks & 0xffff);
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }

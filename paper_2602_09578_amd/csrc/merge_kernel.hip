@@ -2,7 +2,8 @@
 // query head) it combines the partials of the group's prefix chunks and of the sequence's
 // own suffix chunks, in slot order (so the sum order never changes between runs):
 //   m* = max_i m_i,  out = sum_i O_i 2^(m_i - m*) / sum_i l_i 2^(m_i - m*)
-// (m in log2 units).  A row without any token gives zeros.
+// (m in log2 units).  A row without any token gives zeros.  Rows of a sequence whose own tokens
+// were a single item of the suffix kernel are not touched: that kernel has written them.
 //
 // The kernel is a chain of dependent loads with almost no arithmetic, so it is organised to
 // keep that chain short: the plan kernel has already stored each sequence's chunk counts
@@ -26,6 +27,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(AttnArgs a) {
   const int s = row / a.Hq;
   const int info = a.seq_chunks[s];
   const int npc = info & 0xffff, nsc = info >> 16;
+  // a sequence whose own tokens are one item of the suffix kernel (more than kShortTokens tokens
+  // in one chunk) was finished there
+  if (nsc == 1 && min(max(a.suffix_lens[s], 0), a.max_sp * kPage) > kShortTokens) return;
   const int n = npc + nsc;
   const int nslot = a.NCp + a.NCs;
   const float2* ml = a.partial_ml + (size_t)row * nslot;
