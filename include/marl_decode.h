@@ -141,11 +141,14 @@ int marl_workspace_bytes(const marl_attn_shape* shape, size_t* bytes);
  * Work: a plan kernel builds the group->sequences CSR and two work lists (prefix items per
  * group, suffix items per sequence, each at most a chunk of tokens, longest first); a
  * prefix kernel streams each group's prefix KV once for all of the group's query rows; a
- * suffix kernel streams each sequence's own KV (items of at most 128 tokens are taken, one per
- * wave, by the prefix kernel's workgroups before they start on the prefix items); a merge kernel combines the per-chunk
- * (max, sum, output) partials in a fixed order, so results are bit-identical across runs.  A sequence whose
- * own tokens form a single item of the suffix kernel is finished there (the same formula and order,
- * applied to the group's prefix partials and the item's own result) and skipped by the merge kernel.
+ * suffix kernel streams each sequence's own KV in items of more than 128 tokens; a merge kernel
+ * combines the per-chunk (max, sum, output) partials in a fixed order, so results are
+ * bit-identical across runs.  A sequence whose own tokens form a single item never writes a
+ * suffix partial: the kernel that processes the item (the suffix kernel, or for items of at most
+ * 128 tokens the first phase of the merge kernel, one item per wave) applies the merge formula to
+ * the group's prefix partials and its own result and writes the output rows.  Short items of
+ * sequences with several suffix chunks are taken by the prefix kernel's workgroups before they
+ * start on the prefix items.
  */
 int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t workspace_bytes,
                      const void* q, const void* k_pages, const void* v_pages,

@@ -11,7 +11,7 @@ _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 LIB_DIR = os.path.join(_PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libmarl_decode.so")
-SOURCES = ["api.hip", "plan_kernel.hip", "attn_kernels.hip", "merge_kernel.hip", "logprob_kernels.hip",
+SOURCES = ["api.hip", "plan_kernel.hip", "attn_kernels.hip", "logprob_kernels.hip",
            "kv_cache_kernels.hip", "sample_kernels.hip", "grpo_kernels.hip", "prefill_kernels.hip", "balancer.hip", "pack_kernels.hip", "page_pool.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

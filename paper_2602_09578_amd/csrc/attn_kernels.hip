@@ -51,10 +51,10 @@ struct ItemLds {
 //   NW = 1: called by one wave on its own (no LDS, no barrier): for short items.
 //   row_index[qt]: for this lane's q-row (i) of tile qt, seq*Hq + head, or -1 if the row
 //   does not exist.  slot: partial slot of this chunk.
-//   finish (NW = 4 only, workgroup-uniform): the item holds all of the sequence's own tokens,
-//   so the rows' only other partials are the n_prefix_partials prefix partials of its group,
-//   which an earlier kernel has completed: the workgroup merges them with its own result (the
-//   merge kernel's formula and order: prefix slots first) and writes the final output rows
+//   finish (uniform over the callers): the item holds all of the sequence's own tokens, so the
+//   rows' only other partials are the n_prefix_partials prefix partials of its group, which an
+//   earlier kernel has completed: they are merged with the item's own result (the merge
+//   kernel's formula and order: prefix slots first) and the final output rows are written
 //   instead of a partial.
 template <int MT, int NW>
 __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* __restrict__ table_row,
@@ -294,11 +294,48 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
 #pragma unroll
     for (int qt = 0; qt < MT; ++qt) {
       if (row_index[qt] >= 0) {
-        const size_t ps = (size_t)row_index[qt] * nslot + slot;
-        float* dst = a.partial_o + ps * kD + 4 * j;
+        if (!finish) {
+          const size_t ps = (size_t)row_index[qt] * nslot + slot;
+          float* dst = a.partial_o + ps * kD + 4 * j;
 #pragma unroll
-        for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct];
-        if (j == 0) a.partial_ml[ps] = make_float2(m_run[qt], l_run[qt]);
+          for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct];
+          if (j == 0) a.partial_ml[ps] = make_float2(m_run[qt], l_run[qt]);
+        } else {
+          const size_t p0 = (size_t)row_index[qt] * nslot;
+          float mstar = m_run[qt];
+          for (int k = 0; k < n_prefix_partials; ++k) mstar = fmaxf(mstar, a.partial_ml[p0 + k].x);
+          float denom = 0.f;
+          f32x4 sum[8];
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) sum[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int k = 0; k < n_prefix_partials; ++k) {
+            const float2 v = a.partial_ml[p0 + k];
+            const float f = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(v.x - mstar);
+            denom = __builtin_fmaf(v.y, f, denom);
+            const float* src = a.partial_o + (p0 + k) * kD + 4 * j;
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct) sum[ct] += *reinterpret_cast<const f32x4*>(src + 16 * ct) * f;
+          }
+          {
+            const float f = (m_run[qt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[qt] - mstar);
+            denom = __builtin_fmaf(l_run[qt], f, denom);
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct) sum[ct] += acc[qt][ct] * f;
+          }
+          const float inv = denom > 0.f ? 1.0f / denom : 0.f;
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) {
+            const f32x4 res = sum[ct] * inv;
+            const size_t at = (size_t)row_index[qt] * kD + 16 * ct + 4 * j;
+            if (a.out_dtype == MARL_OUT_F32) {
+              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + at) = res;
+            } else {
+              typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+              const bf16x4 v = {(__bf16)res[0], (__bf16)res[1], (__bf16)res[2], (__bf16)res[3]};
+              *reinterpret_cast<bf16x4*>(reinterpret_cast<uint16_t*>(a.out) + at) = v;
+            }
+          }
+        }
       }
     }
   }
@@ -316,11 +353,15 @@ __device__ __forceinline__ void process_item(const AttnArgs& a, const int32_t* _
 //   short_suffix_items:  short items, one per wave, split round-robin over all waves of the
 //                        grid with no LDS traffic, barrier or atomic, so a batch of tiny
 //                        sequences does not pay a workgroup's fixed costs per sequence.
-//                        It runs as the first phase of the PREFIX kernel's workgroups: as a
-//                        phase of the suffix kernel it slowed the long items' hot loop down
-//                        by a few percent (shared register allocation), as a kernel of its
-//                        own it cost one more launch per call, and at the end of any kernel
-//                        its latency-bound rounds stretch the tail.
+//                        Where they run: a sequence whose own tokens are one short item (the
+//                        usual case) is finished in the first phase of the MERGE kernel, after
+//                        the prefix partials are complete: its rows never pass through a partial.
+//                        The short items of sequences with several suffix chunks must be
+//                        partials before the merge kernel starts: they run as the first phase of
+//                        the PREFIX kernel's workgroups (as a phase of the suffix kernel they
+//                        slowed the long items' hot loop down by a few percent through the
+//                        shared register allocation, and a kernel of their own cost one more
+//                        launch per call).
 // ---------------------------------------------------------------------------------------
 #ifndef MARL_SUFFIX_WAVES_PER_EU
 #define MARL_SUFFIX_WAVES_PER_EU 3
@@ -364,6 +405,11 @@ void suffix_kernel(AttnArgs a) {
 // (W = waves in the grid) with no LDS, no barrier and no atomic: the entries are sorted by
 // size, so a round-robin split is balanced, and a shared queue counter would serialise
 // thousands of waves on one address.  The next record is fetched while the current item runs.
+// kFinish = false (first phase of the prefix kernel): the items of sequences with several
+// suffix chunks, as partials.  kFinish = true (first phase of the merge kernel, after the
+// prefix partials are complete): the items of sequences whose own tokens are that one item,
+// finished to output rows, so that they never travel through a partial.
+template <bool kFinish>
 __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int& bad_page) {
   const int n_long = a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] * a.Hkv;
   const int n_work = a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] * a.Hkv;
@@ -378,10 +424,13 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int& bad_p
     const int4 nrec = nxt < n_work ? a.suffix_items[nxt / a.Hkv] : make_int4(0, 0, 0, 0);
     const int kvh = cur % a.Hkv;
     const int s = rec.x;
-    const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
-    ItemLds<1>* no_lds = nullptr;   // the one-wave path never touches it
-    process_item<1, 1>(a, a.suffix_table + (size_t)s * a.max_sp, rec.y, rec.z, kvh, row_index,
-                       a.NCp + rec.y / a.Cs, *no_lds, bad_page);
+    const int chunks = ld_uniform(a.seq_chunks + s);
+    if (((chunks >> 16) == 1) == kFinish) {
+      const int row_index[1] = {i < a.R ? s * a.Hq + kvh * a.R + i : -1};
+      ItemLds<1>* no_lds = nullptr;   // the one-wave path never touches it
+      process_item<1, 1>(a, a.suffix_table + (size_t)s * a.max_sp, rec.y, rec.z, kvh, row_index,
+                         a.NCp + rec.y / a.Cs, *no_lds, bad_page, kFinish, chunks & 0xffff);
+    }
     cur = nxt;
     rec = nrec;
   }
@@ -642,7 +691,7 @@ __device__ __forceinline__ void prefix_kernel_body(const AttnArgs& a) {
   // The short suffix items go first: each round is a chain of dependent memory accesses with
   // little data, which is cheap while every workgroup has other work to overlap it with and
   // expensive at the tail of a kernel, where only a few workgroups are left.
-  short_suffix_items(a, bad_page);
+  short_suffix_items<false>(a, bad_page);
   __syncthreads();
   for (bool first = true;; first = false) {   // first item = block index, as in the suffix kernel
     int qi = blockIdx.x;
@@ -670,6 +719,93 @@ void prefix_kernel(AttnArgs a) { prefix_kernel_body<4>(a); }
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void prefix_kernel_wide(AttnArgs a) { prefix_kernel_body<8>(a); }
 
+// ---------------------------------------------------------------------------------------
+// Merge kernel: the second reduction of split-KV decode attention.  For every (sequence,
+// query head) it combines the partials of the group's prefix chunks and of the sequence's
+// own suffix chunks, in slot order (so the sum order never changes between runs):
+//   m* = max_i m_i,  out = sum_i O_i 2^(m_i - m*) / sum_i l_i 2^(m_i - m*)
+// (m in log2 units).  A row without any token gives zeros.  Rows of a sequence whose own tokens
+// are a single item are written where that item is processed (the suffix kernel, or this
+// kernel's first phase for short items) and are not touched by the row loop.
+//
+// The kernel is a chain of dependent loads with almost no arithmetic, so it is organised to
+// keep that chain short: the plan kernel has already stored each sequence's chunk counts
+// (one load instead of group id -> prefix length), half a wave handles one row with 16-byte
+// loads, and the first four partials of a row (max/sum and output) are all requested before
+// any of them is used.  Every lane recomputes the few scalar weights itself: no shuffles.
+// ---------------------------------------------------------------------------------------
+constexpr int kMergeThreads = 256;
+constexpr int kRowsPerBlock = kMergeThreads / 32;
+constexpr int kEager = 4;   // partials fetched up front
+
+__global__ __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void merge_kernel(AttnArgs a) {
+  // first the sequences whose own tokens are one short item: attention over those tokens and
+  // the merge with the group's prefix partials in one go, one item per wave
+  {
+    int bad_page = 0;
+    short_suffix_items<true>(a, bad_page);
+    if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
+  }
+  const int sub = threadIdx.x & 31;   // lane within the half wave: channels 4*sub .. 4*sub+3
+  const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 5);
+  if (row >= a.NS * a.Hq) return;
+  const int s = row / a.Hq;
+  const int info = a.seq_chunks[s];
+  const int npc = info & 0xffff, nsc = info >> 16;
+  // a sequence whose own tokens are one item was finished where that item was processed: above
+  // (at most kShortTokens tokens) or in the suffix kernel
+  if (nsc == 1) return;
+  const int n = npc + nsc;
+  const int nslot = a.NCp + a.NCs;
+  const float2* ml = a.partial_ml + (size_t)row * nslot;
+  const float* po = a.partial_o + (size_t)row * nslot * kD + 4 * sub;
+  auto slot_of = [&](int k) { return k < npc ? k : a.NCp + (k - npc); };
+
+  float2 mlk[kEager];
+  f32x4 ok[kEager];
+#pragma unroll
+  for (int k = 0; k < kEager; ++k) {
+    mlk[k] = make_float2(-INFINITY, 0.f);
+    ok[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (k < n) {
+      const int sl = slot_of(k);
+      mlk[k] = ml[sl];
+      ok[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(po + (size_t)sl * kD));
+    }
+  }
+  float mstar = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < kEager; ++k) mstar = fmaxf(mstar, mlk[k].x);
+  for (int k = kEager; k < n; ++k) mstar = fmaxf(mstar, ml[slot_of(k)].x);
+
+  float denom = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < kEager; ++k) {
+    const float f = (mlk[k].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mlk[k].x - mstar);
+    denom = __builtin_fmaf(mlk[k].y, f, denom);
+    acc += ok[k] * f;
+  }
+  for (int k = kEager; k < n; ++k) {
+    const int sl = slot_of(k);
+    const float2 v = ml[sl];
+    const f32x4 o = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(po + (size_t)sl * kD));
+    const float f = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(v.x - mstar);
+    denom = __builtin_fmaf(v.y, f, denom);
+    acc += o * f;
+  }
+  f32x4 r = {0.f, 0.f, 0.f, 0.f};
+  if (n > 0 && denom > 0.f) r = acc * (1.0f / denom);
+  if (a.out_dtype == MARL_OUT_F32) {
+    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + (size_t)row * kD + 4 * sub) = r;
+  } else {
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    const bf16x4 v = {(__bf16)r[0], (__bf16)r[1], (__bf16)r[2], (__bf16)r[3]};
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<uint16_t*>(a.out) + (size_t)row * kD + 4 * sub) = v;
+  }
+}
+
 }  // namespace
 
 int prefix_blocks_per_cu(bool wide) {
@@ -694,4 +830,12 @@ hipError_t launch_suffix(const AttnArgs& a, int grid, hipStream_t st) {
   hipLaunchKernelGGL(suffix_kernel, dim3(grid), dim3(kSuffixWaves * 64), 0, st, a);
   return hipGetLastError();
 }
+hipError_t launch_merge(const AttnArgs& a, hipStream_t st) {
+  const long rows = (long)a.NS * a.Hq;
+  if (rows == 0) return hipSuccess;
+  const int grid = (int)((rows + kRowsPerBlock - 1) / kRowsPerBlock);
+  hipLaunchKernelGGL(merge_kernel, dim3(grid), dim3(kMergeThreads), 0, st, a);
+  return hipGetLastError();
+}
+
 }  // namespace marl
