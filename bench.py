@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0
 # factors a copy kernel of known size gives).  Valid only for the kernel source and flags it was taken
 # with: reported as null when either has changed since.
 SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5556.9e6 + 14.1e6,
-                  "kernel_sources_sha256": "05dc0bb9c597a0d43e3b119e670b61835c5b7015bb5acee88affbae871833d8b"}
+                  "kernel_sources_sha256": "e77282e3c056186aa3d70d62064b0be2a6b236159a154a4c4827feb69caca86d"}
 SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 

@@ -1,8 +1,9 @@
 // Decode attention over the paged KV cache: the prefix kernel (a group's prefix KV is
-// streamed once and applied to all of the group's query rows) and the suffix kernel (each
-// sequence's own generated tokens).  Both produce flash-decoding style partials
-// (running max, running sum, unnormalised output) per (query row, chunk of tokens), which
-// the merge kernel combines.
+// streamed once and applied to all of the group's query rows), the suffix kernel (each
+// sequence's own generated tokens) and the merge kernel.  The first two produce
+// flash-decoding style partials (running max, running sum, unnormalised output) per (query
+// row, chunk of tokens), which the merge kernel combines; a sequence whose own tokens are a
+// single work item is finished by whoever processes that item instead.
 //
 // Context in the paper: rollout is memory-bound on KV caches (Section 4.1), every prompt is
 // expanded into several samples that share its prefix (Section 5.1) and lengths are skewed
