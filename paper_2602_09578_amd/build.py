@@ -51,19 +51,5 @@ def build_library(verbose: bool = False, extra_flags=(), out_path: str = LIB_PAT
     return out_path
 
 
-PROBE_PATH = os.path.join(LIB_DIR, "hbm_probe")
-
-
-def build_probe() -> str:
-    """The HBM calibration program (streaming read ceilings, copy kernel of known size)."""
-    os.makedirs(LIB_DIR, exist_ok=True)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", os.path.join(CSRC, "hbm_probe.hip"), "-o", PROBE_PATH]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hbm_probe build failed:\n" + r.stdout)
-    return PROBE_PATH
-
-
 if __name__ == "__main__":
     print(build_library(verbose=True, extra_flags=sys.argv[1:]))
-    print(build_probe())

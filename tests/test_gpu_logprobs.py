@@ -49,7 +49,17 @@ def test_full_size_qwen7b_rows():
     print("case: logprobs full size", flush=True)
     w = I.WORKLOADS["qwen7b"]
     lp = I.build_logprob_inputs(w.num_seqs, w.vocab, w.logit_sigma, w.seed, device="cuda")
-    print(check(lp))
+    print("qwen7b log-probs: all", w.num_seqs, "rows, max |delta| =", check(lp), flush=True)
+
+
+def test_full_size_long32b_rows():
+    """The long-context workload's own call: 256 rows x 152064, which the library splits into
+    vocabulary slices plus a finishing kernel; every row against the checker."""
+    print("case: logprobs full size long32b", flush=True)
+    w = I.WORKLOADS["long32b"]
+    assert B.marl_logprobs_workspace_bytes(w.num_seqs, w.vocab) > 0      # the sliced path
+    lp = I.build_logprob_inputs(w.num_seqs, w.vocab, w.logit_sigma, w.seed, device="cuda")
+    print("long32b log-probs: all", w.num_seqs, "rows, max |delta| =", check(lp), flush=True)
 
 
 def test_training_shape_sampled_rows():
