@@ -81,6 +81,91 @@ def cpu_baseline(attn_dev: I.AttnInputs, lp_dev: I.LogprobInputs, seq_stride: in
             "attn_seqs_per_s": len(pick) / t_attn, "logprob_rows_per_s": rows / t_lp}
 
 
+def dominant_kernel_roofline(w, attn, call, stage_ms):
+    """Roofline entry of the attention kernel that takes the most time of a call."""
+    bpt = attn.kv_bytes_per_token()
+    # the suffix kernel processes the suffix items of more than 128 tokens (the shorter ones are taken
+    # by the workgroups of the merge and prefix kernels): its algorithmic bytes per launch
+    S = attn.suffix_lens.cpu().numpy().astype(np.int64)
+    Cs = call.layout.suffix_chunk_tokens
+    tail = S % Cs
+    long_tok = int(((S // Cs) * Cs * (Cs > 128) + tail * (tail > 128)).sum())
+    if long_tok and stage_ms["suffix"] >= stage_ms["prefix"]:
+        gbps = long_tok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
+        return {"kernel": "suffix_kernel", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": suffix_traffic(w.name),
+                "algorithmic_bytes_per_launch": long_tok * bpt, "avg_launch_ms": stage_ms["suffix"]}
+    # the prefix kernel dominates (prefix-dominated group sampling): its QK^T and PV products against the
+    # dense bf16 matrix peak, and its unique prefix bytes against the HBM peak
+    counts = np.bincount(attn.group_of_seq.cpu().numpy(), minlength=attn.num_groups)
+    P = attn.prefix_lens.cpu().numpy().astype(np.int64)
+    flops = int(4 * 128 * w.Hq * (P * counts).sum())
+    tf = flops / (stage_ms["prefix"] * 1e-3) / 1e12
+    pbytes = int(P.sum()) * bpt
+    return {"kernel": "prefix_kernel", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+            "frac": tf / 2500.0, "traffic": None, "algorithmic_flops_per_launch": flops,
+            "avg_launch_ms": stage_ms["prefix"],
+            "hbm_frac_on_unique_prefix_bytes": pbytes / (stage_ms["prefix"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
+def measure_workload(name: str, dev, iters: int = 20, warmup: int = 3):
+    """One workload's decode attention (and its log-prob call where the workload names one), outside the
+    headline timed region: per-call times from events around each call, then per-kernel averages from
+    the library's own event timing over `iters` further calls."""
+    w = I.WORKLOADS[name]
+    attn = I.build_attn_inputs(w, device=dev)
+    call = B.prepare_attn(attn, B.MARL_OUT_BF16)
+    for _ in range(warmup):
+        B.run_attn(attn, call)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for e0, e1 in evs:
+        e0.record()
+        B.run_attn(attn, call)
+        e1.record()
+    torch.cuda.synchronize()
+    t = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    med = t[len(t) // 2]
+    B.marl_profile_begin(iters)
+    for _ in range(iters):
+        B.run_attn(attn, call)
+    torch.cuda.synchronize()
+    stage_ms, n_attn, _ = B.marl_profile_end()
+    assert n_attn == iters and B.marl_attn_read_flags(call.workspace) == 0
+    assert torch.isfinite(call.out.float()).all().item()
+    ptok, stok = attn.unique_kv_tokens()
+    ubytes = (ptok + stok) * attn.kv_bytes_per_token()
+    r = {"num_seqs": w.num_seqs, "unique_kv_bytes": ubytes, "attn_ms_median": med, "attn_ms_min": t[0],
+         "unique_kv_GBps": ubytes / (med * 1e-3) / 1e9,
+         "pct_of_hbm_peak": ubytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS * 100,
+         "seq_steps_per_s": w.num_seqs / (med * 1e-3),
+         "kernel_ms": {k: stage_ms[k] for k in ("plan", "prefix", "suffix", "merge")},
+         "dominant_kernel": dominant_kernel_roofline(w, attn, call, stage_ms)}
+    r["dominant_kernel"].pop("traffic", None)
+    del attn, call
+    if w.vocab:
+        lp = I.build_logprob_inputs(w.num_seqs, w.vocab, w.logit_sigma, w.seed, device=dev)
+        nws = B.marl_logprobs_workspace_bytes(w.num_seqs, w.vocab)
+        ws = B.alloc_workspace(nws, dev) if nws else None
+        out = torch.empty(w.num_seqs, dtype=torch.float32, device=dev)
+        for _ in range(warmup):
+            B.marl_token_logprobs(lp.logits, lp.tokens, lp.temperature, out, ws)
+        for e0, e1 in evs:
+            e0.record()
+            B.marl_token_logprobs(lp.logits, lp.tokens, lp.temperature, out, ws)
+            e1.record()
+        torch.cuda.synchronize()
+        t = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        med = t[len(t) // 2]
+        assert torch.isfinite(out).all().item()
+        r["logprob"] = {"rows": w.num_seqs, "vocab": w.vocab, "ms_median": med,
+                        "rows_per_s": w.num_seqs / (med * 1e-3),
+                        "GBps": w.num_seqs * w.vocab * 2 / (med * 1e-3) / 1e9,
+                        "frac_of_hbm_peak": w.num_seqs * w.vocab * 2 / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        del lp, ws, out
+    torch.cuda.empty_cache()
+    return r
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +173,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen7b", choices=sorted(I.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the per-workload block")
     ap.add_argument("--cpu-seq-stride", type=int, default=1, help="CPU baseline: every n-th sequence")
     ap.add_argument("--cpu-logprob-rows", type=int, default=1 << 30, help="CPU baseline: first n logit rows")
     ap.add_argument("--suffix-chunk", type=int, default=0)
@@ -166,28 +252,7 @@ def main():
     bpt = attn.kv_bytes_per_token()
     attn_ms = stage_ms["plan"] + stage_ms["prefix"] + stage_ms["suffix"] + stage_ms["merge"]
     lp_ms = stage_ms["logprob"] + stage_ms["logprob_finish"]
-    # the suffix kernel processes the suffix items of more than 128 tokens (the shorter ones
-    # are taken by the prefix kernel's workgroups): its algorithmic bytes per launch
-    S = attn.suffix_lens.cpu().numpy().astype(np.int64)
-    Cs = call.layout.suffix_chunk_tokens
-    tail = S % Cs
-    long_tok = int(((S // Cs) * Cs * (Cs > 128) + tail * (tail > 128)).sum())
-    if long_tok:
-        suffix_gbps = long_tok * bpt / (stage_ms["suffix"] * 1e-3) / 1e9
-        roofline = {"kernel": "suffix_kernel", "bound": "hbm", "achieved": suffix_gbps, "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": suffix_gbps / HBM_PEAK_GBPS, "traffic": suffix_traffic(w.name),
-                    "algorithmic_bytes_per_launch": long_tok * bpt, "avg_launch_ms": stage_ms["suffix"]}
-    else:
-        # no item for the suffix kernel (every sequence has at most 128 generated tokens): the prefix
-        # kernel is the dominant one; its QK^T and PV products against the dense bf16 matrix peak
-        flops = 4 * 128 * w.Hq * sum(int(P) * int(n) for P, n in
-                                     zip(attn.prefix_lens.cpu().tolist(),
-                                         np.bincount(attn.group_of_seq.cpu().numpy(), minlength=w.num_groups)))
-        tf = flops / (stage_ms["prefix"] * 1e-3) / 1e12
-        roofline = {"kernel": "prefix_kernel", "bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
-                    "frac": tf / 2500.0, "traffic": None, "algorithmic_flops_per_launch": flops,
-                    "avg_launch_ms": stage_ms["prefix"],
-                    "note": "the launch also processes the short suffix items, which are not in the flops"}
+    roofline = dominant_kernel_roofline(w, attn, call, stage_ms)
     res = {
         "metric": "rollout decode step throughput (paged shared-prefix decode attention + token log-probs)",
         "value": w.num_seqs / (ms_per_step * 1e-3),
@@ -325,6 +390,10 @@ def main():
                           "GBps_read_plus_write": 2 * moved / (t_pack / 3 * 1e-3) / 1e9,
                           "one_copy_per_tensor_ms": t_each / 3}
     del params, packed, views, table
+    # every named workload's attention call (and log-prob call), outside the timed step
+    if not a.no_workloads:
+        torch.cuda.empty_cache()
+        res["workloads"] = {name: measure_workload(name, dev) for name in I.WORKLOADS}
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(attn, lp, seq_stride=a.cpu_seq_stride, lp_rows=a.cpu_logprob_rows)
     print(json.dumps(res))
