@@ -166,6 +166,34 @@ int marl_attn_plan(const marl_attn_shape* shape, void* workspace, size_t workspa
 int marl_attn_read_flags(const void* workspace, int32_t* flags_host, void* stream);
 
 /*
+ * marl_decode_attn for callers that cannot allocate device memory or hold a workspace of their
+ * own: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, same kernels and bit-identical results as marl_decode_attn; the workspace is a
+ * fixed array of MARL_STATIC_WORKSPACE_BYTES that is part of the library's code object (every GPU
+ * the library runs on holds one copy from the first use there until the process ends).  The call
+ * allocates nothing and frees nothing; its first call on a device looks the array's address up.
+ *   - A shape whose marl_workspace_bytes() exceeds MARL_STATIC_WORKSPACE_BYTES is rejected with
+ *     MARL_WORKSPACE_TOO_SMALL on the host, before any HIP call (shrink the batch, or use
+ *     marl_decode_attn with a workspace of the caller's).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race; order them on one stream.  The array keeps the last call's
+ *     work list and partials; the plan kernel clears the counters it needs at zero, nothing else
+ *     needs clearing.
+ *   - flags: device int32*, may be NULL; after the call's work it holds the MARL_FLAG_* word of
+ *     this call (what marl_attn_read_flags reads from a caller's workspace), copied on `stream`
+ *     without synchronising.  Must be 4-byte aligned.
+ *   - Per-kernel event timing (marl_profile_begin) never covers this entry point.
+ * The device that is current at the call must be the one that owns `stream` and the operands.
+ */
+#define MARL_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+int marl_decode_attn_static(const marl_attn_shape* shape,
+                            const void* q, const void* k_pages, const void* v_pages,
+                            const int32_t* prefix_block_table, const int32_t* suffix_block_table,
+                            const int32_t* prefix_lens, const int32_t* suffix_lens,
+                            const int32_t* group_of_seq, float scale, void* out, int32_t* flags,
+                            void* stream);
+
+/*
  * KV-cache maintenance for the decode loop (what happens before marl_decode_attn in a decode
  * iteration).  Both are pure data movement; results are bit-exact.
  *

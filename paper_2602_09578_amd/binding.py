@@ -88,6 +88,7 @@ def load_library(build_if_missing: bool = True):
     lib.marl_attn_plan_layout_for.argtypes = [PS, PL]
     lib.marl_workspace_bytes.argtypes = [PS, ctypes.POINTER(SZ)]
     lib.marl_decode_attn.argtypes = [PS, VP, SZ, VP, VP, VP, VP, VP, VP, VP, VP, ctypes.c_float, VP, VP]
+    lib.marl_decode_attn_static.argtypes = [PS, VP, VP, VP, VP, VP, VP, VP, VP, ctypes.c_float, VP, VP, VP]
     lib.marl_attn_plan.argtypes = [PS, VP, SZ, VP, VP, VP, VP]
     lib.marl_attn_read_flags.argtypes = [VP, ctypes.POINTER(I32), VP]
     lib.marl_logprobs_workspace_bytes.argtypes = [I32, I32, ctypes.POINTER(SZ)]
@@ -134,7 +135,8 @@ def load_library(build_if_missing: bool = True):
     lib.marl_pack_plan.restype = lib.marl_pack_tensors.restype = lib.marl_unpack_tensors.restype = ctypes.c_int
     lib.marl_profile_begin.argtypes = [I32]
     lib.marl_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I32), ctypes.POINTER(I32)]
-    for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_attn_plan",
+    for f in ("marl_attn_plan_layout_for", "marl_workspace_bytes", "marl_decode_attn", "marl_decode_attn_static",
+              "marl_attn_plan",
               "marl_attn_read_flags", "marl_logprobs_workspace_bytes", "marl_token_logprobs",
               "marl_profile_begin", "marl_profile_end"):
         getattr(lib, f).restype = ctypes.c_int
@@ -201,6 +203,23 @@ def marl_decode_attn(shape: AttnShape, workspace: torch.Tensor, q, k_pages, v_pa
         _ptr(prefix_block_table), _ptr(suffix_block_table), _ptr(prefix_lens), _ptr(suffix_lens),
         _ptr(group_of_seq), float(scale), _ptr(out), _stream(out.device))
     _check(rc, "marl_decode_attn")
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20   # MARL_STATIC_WORKSPACE_BYTES of the header
+
+
+def marl_decode_attn_static(shape: AttnShape, q, k_pages, v_pages, prefix_block_table, suffix_block_table,
+                            prefix_lens, suffix_lens, group_of_seq, scale: float, out: torch.Tensor,
+                            flags: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """marl_decode_attn on the library's own fixed workspace (no allocation in the call)."""
+    _require_cuda(q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens, suffix_lens,
+                  group_of_seq, out, flags)
+    rc = load_library().marl_decode_attn_static(
+        ctypes.byref(shape), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(prefix_block_table),
+        _ptr(suffix_block_table), _ptr(prefix_lens), _ptr(suffix_lens), _ptr(group_of_seq), float(scale),
+        _ptr(out), _ptr(flags), _stream(out.device))
+    _check(rc, "marl_decode_attn_static")
     return out
 
 

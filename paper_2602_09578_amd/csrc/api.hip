@@ -9,6 +9,12 @@
 
 #include "marl_internal.h"
 
+// Workspace of marl_decode_attn_static, the entry point for callers that cannot allocate.
+// One array per GPU, part of the library's code object: the device keeps it from the moment the
+// library is loaded there until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; kernels and copies get the address that call returns, per device.
+static __device__ __align__(256) unsigned char scratch[MARL_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 thread_local std::string g_last_hip_error;
@@ -144,15 +150,9 @@ void query_device() {
   g_suffix_bpc = marl::suffix_blocks_per_cu();
 }
 
-int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArgs& a) {
-  marl_attn_plan_layout L;
-  const int rc = make_layout(s, &L);
-  if (rc != MARL_OK) return rc;
-  if (!ws) return MARL_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return MARL_INVALID_ARG;
-  if (ws_bytes < L.total_bytes) return MARL_WORKSPACE_TOO_SMALL;
+// Points the workspace arrays of `a` into `ws` as the layout says.
+void point_workspace(const marl_attn_plan_layout& L, void* ws, marl::AttnArgs& a) {
   char* w = static_cast<char*>(ws);
-  memset(&a, 0, sizeof a);
   a.counters = reinterpret_cast<int32_t*>(w + L.counters_off);
   a.group_count = reinterpret_cast<int32_t*>(w + L.group_count_off);
   a.group_start = reinterpret_cast<int32_t*>(w + L.group_start_off);
@@ -164,6 +164,11 @@ int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArg
   a.prefix_items = reinterpret_cast<int4*>(w + L.prefix_items_off);
   a.partial_ml = reinterpret_cast<float2*>(w + L.partial_ml_off);
   a.partial_o = reinterpret_cast<float*>(w + L.partial_o_off);
+}
+
+// The shape-derived fields of `a` (everything but pointers).
+void fill_shape_args(const marl_attn_shape* s, const marl_attn_plan_layout& L, marl::AttnArgs& a) {
+  memset(&a, 0, sizeof a);
   a.NS = s->num_seqs;
   a.NG = s->num_groups;
   a.Hq = s->num_q_heads;
@@ -178,6 +183,101 @@ int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArg
   a.NCp = L.prefix_slots;
   a.qblock_rows = L.rows_per_qblock;
   a.out_dtype = s->out_dtype;
+}
+
+int fill_args(const marl_attn_shape* s, void* ws, size_t ws_bytes, marl::AttnArgs& a) {
+  marl_attn_plan_layout L;
+  const int rc = make_layout(s, &L);
+  if (rc != MARL_OK) return rc;
+  if (!ws) return MARL_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return MARL_INVALID_ARG;
+  if (ws_bytes < L.total_bytes) return MARL_WORKSPACE_TOO_SMALL;
+  fill_shape_args(s, L, a);
+  point_workspace(L, ws, a);
+  return MARL_OK;
+}
+
+// Validates the operands of a decode-attention call (host-only) and stores them in `a`, whose
+// shape fields are already set.
+int take_attn_operands(marl::AttnArgs& a, const void* q, const void* k_pages, const void* v_pages,
+                       const int32_t* prefix_block_table, const int32_t* suffix_block_table,
+                       const int32_t* prefix_lens, const int32_t* suffix_lens,
+                       const int32_t* group_of_seq, float scale, void* out) {
+  if (!isfinite(scale)) return MARL_INVALID_ARG;
+  if (a.NS > 0 && (!q || !out || !suffix_lens || !group_of_seq || !k_pages || !v_pages)) return MARL_INVALID_ARG;
+  if (a.NS > 0 && a.max_sp > 0 && !suffix_block_table) return MARL_INVALID_ARG;
+  if (a.NG > 0 && (!prefix_lens || (a.max_pp > 0 && !prefix_block_table))) return MARL_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)) return MARL_INVALID_ARG;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_pages = static_cast<const uint16_t*>(k_pages);
+  a.v_pages = static_cast<const uint16_t*>(v_pages);
+  a.prefix_table = prefix_block_table;
+  a.suffix_table = suffix_block_table;
+  a.prefix_lens = prefix_lens;
+  a.suffix_lens = suffix_lens;
+  a.group_of_seq = group_of_seq;
+  a.scale = scale;
+  a.out = out;
+  return MARL_OK;
+}
+
+// Enqueues the kernels of one decode-attention call.  `may_time`: the call takes part in the
+// per-kernel event timing when that is switched on (events are created then).
+int enqueue_decode_attn(const marl::AttnArgs& a, hipStream_t st, bool may_time) {
+  std::call_once(g_dev_once, query_device);
+  if (g_dev_err != hipSuccess) return hip_fail(g_dev_err, "device query");
+
+  std::unique_lock<std::mutex> lock(g_prof.mu, std::defer_lock);
+  bool timed = false;
+  if (may_time && g_prof.on) {
+    lock.lock();
+    timed = g_prof.on && g_prof.attn_calls < g_prof.max_calls;
+    if (timed) ++g_prof.attn_calls; else lock.unlock();
+  }
+  StageTimer T(st, timed);
+  hipError_t e;
+  if ((e = T.run(MARL_STAGE_PLAN, [&] { return marl::launch_plan(a, st); })) != hipSuccess)
+    return hip_fail(e, "plan kernel");
+  {  // always launched: its workgroups also process the short suffix items
+    if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * (a.qblock_rows == marl::kRowsPerQBlockWide ? g_prefix_wide_bpc : g_prefix_bpc), st); })) != hipSuccess)
+      return hip_fail(e, "prefix kernel");
+  }
+  // the suffix kernel takes the items of more than kShortTokens tokens: none can exist when
+  // neither a table row nor a chunk holds that many
+  if ((long)a.max_sp * marl::kPage > marl::kShortTokens && a.Cs > marl::kShortTokens) {
+    if ((e = T.run(MARL_STAGE_SUFFIX, [&] { return marl::launch_suffix(a, g_num_cus * g_suffix_bpc, st); })) != hipSuccess)
+      return hip_fail(e, "suffix kernel");
+  }
+  if ((e = T.run(MARL_STAGE_MERGE, [&] { return marl::launch_merge(a, st); })) != hipSuccess)
+    return hip_fail(e, "merge kernel");
+  return MARL_OK;
+}
+
+// ---- workspace for callers that cannot allocate (the array itself is at the top of this file) ----
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Plain one-word store, for a flag word that no kernel of an empty call would write.
+__global__ void store_word_kernel(int32_t* dst, int32_t value) { *dst = value; }
+
+int static_scratch_of_current_device(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return MARL_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p || reinterpret_cast<uintptr_t>(p) % 256 != 0) {
+      g_last_hip_error = "hipGetSymbolAddress(scratch): unusable address";
+      return MARL_HIP_ERROR;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
   return MARL_OK;
 }
 
@@ -233,52 +333,52 @@ int marl_decode_attn(const marl_attn_shape* shape, void* workspace, size_t works
                      const int32_t* prefix_lens, const int32_t* suffix_lens,
                      const int32_t* group_of_seq, float scale, void* out, void* stream) {
   marl::AttnArgs a;
-  const int rc = fill_args(shape, workspace, workspace_bytes, a);
+  int rc = fill_args(shape, workspace, workspace_bytes, a);
   if (rc != MARL_OK) return rc;
-  if (!isfinite(scale)) return MARL_INVALID_ARG;
-  if (a.NS > 0 && (!q || !out || !suffix_lens || !group_of_seq || !k_pages || !v_pages)) return MARL_INVALID_ARG;
-  if (a.NS > 0 && a.max_sp > 0 && !suffix_block_table) return MARL_INVALID_ARG;
-  if (a.NG > 0 && (!prefix_lens || (a.max_pp > 0 && !prefix_block_table))) return MARL_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)) return MARL_INVALID_ARG;
+  rc = take_attn_operands(a, q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens,
+                          suffix_lens, group_of_seq, scale, out);
+  if (rc != MARL_OK) return rc;
   if (a.NS == 0) return MARL_OK;
-  a.q = static_cast<const uint16_t*>(q);
-  a.k_pages = static_cast<const uint16_t*>(k_pages);
-  a.v_pages = static_cast<const uint16_t*>(v_pages);
-  a.prefix_table = prefix_block_table;
-  a.suffix_table = suffix_block_table;
-  a.prefix_lens = prefix_lens;
-  a.suffix_lens = suffix_lens;
-  a.group_of_seq = group_of_seq;
-  a.scale = scale;
-  a.out = out;
+  return enqueue_decode_attn(a, static_cast<hipStream_t>(stream), /*may_time=*/true);
+}
+
+int marl_decode_attn_static(const marl_attn_shape* shape,
+                            const void* q, const void* k_pages, const void* v_pages,
+                            const int32_t* prefix_block_table, const int32_t* suffix_block_table,
+                            const int32_t* prefix_lens, const int32_t* suffix_lens,
+                            const int32_t* group_of_seq, float scale, void* out, int32_t* flags,
+                            void* stream) {
+  // host-only checks first: the shape, its workspace need against the fixed capacity, the operands
+  marl_attn_plan_layout L;
+  int rc = make_layout(shape, &L);
+  if (rc != MARL_OK) return rc;
+  if (L.total_bytes > MARL_STATIC_WORKSPACE_BYTES) return MARL_WORKSPACE_TOO_SMALL;
+  marl::AttnArgs a;
+  fill_shape_args(shape, L, a);
+  rc = take_attn_operands(a, q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens,
+                          suffix_lens, group_of_seq, scale, out);
+  if (rc != MARL_OK) return rc;
+  if (reinterpret_cast<uintptr_t>(flags) % 4 != 0) return MARL_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
-
-  std::call_once(g_dev_once, query_device);
-  if (g_dev_err != hipSuccess) return hip_fail(g_dev_err, "device query");
-
-  std::unique_lock<std::mutex> lock(g_prof.mu, std::defer_lock);
-  bool timed = false;
-  if (g_prof.on) {
-    lock.lock();
-    timed = g_prof.on && g_prof.attn_calls < g_prof.max_calls;
-    if (timed) ++g_prof.attn_calls; else lock.unlock();
+  if (a.NS == 0) {
+    if (flags) {   // no kernel of the call runs, so none could have set a flag
+      hipLaunchKernelGGL(store_word_kernel, dim3(1), dim3(1), 0, st, flags, 0);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return hip_fail(e, "flag store kernel");
+    }
+    return MARL_OK;
   }
-  StageTimer T(st, timed);
-  hipError_t e;
-  if ((e = T.run(MARL_STAGE_PLAN, [&] { return marl::launch_plan(a, st); })) != hipSuccess)
-    return hip_fail(e, "plan kernel");
-  {  // always launched: its workgroups also process the short suffix items
-    if ((e = T.run(MARL_STAGE_PREFIX, [&] { return marl::launch_prefix(a, g_num_cus * (a.qblock_rows == marl::kRowsPerQBlockWide ? g_prefix_wide_bpc : g_prefix_bpc), st); })) != hipSuccess)
-      return hip_fail(e, "prefix kernel");
+  void* ws = nullptr;
+  rc = static_scratch_of_current_device(&ws);
+  if (rc != MARL_OK) return rc;
+  point_workspace(L, ws, a);   // the plan kernel clears the counters and flags it finds there
+  rc = enqueue_decode_attn(a, st, /*may_time=*/false);
+  if (rc != MARL_OK) return rc;
+  if (flags) {
+    const hipError_t e = hipMemcpyAsync(flags, a.counters + MARL_CTR_FLAGS, sizeof(int32_t),
+                                        hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) return hip_fail(e, "copy flags");
   }
-  // the suffix kernel takes the items of more than kShortTokens tokens: none can exist when
-  // neither a table row nor a chunk holds that many
-  if ((long)a.max_sp * marl::kPage > marl::kShortTokens && a.Cs > marl::kShortTokens) {
-    if ((e = T.run(MARL_STAGE_SUFFIX, [&] { return marl::launch_suffix(a, g_num_cus * g_suffix_bpc, st); })) != hipSuccess)
-      return hip_fail(e, "suffix kernel");
-  }
-  if ((e = T.run(MARL_STAGE_MERGE, [&] { return marl::launch_merge(a, st); })) != hipSuccess)
-    return hip_fail(e, "merge kernel");
   return MARL_OK;
 }
 
