@@ -37,7 +37,8 @@ typedef enum marl_status {
   MARL_INVALID_ARG = -1,   /* null pointer, negative count, Hq % Hkv != 0, non-finite scalar */
   MARL_UNSUPPORTED = -2,   /* head_dim != 128, page_size != 16, unknown out_dtype, bad chunk */
   MARL_WORKSPACE_TOO_SMALL = -3,
-  MARL_HIP_ERROR = -4      /* a launch failed; marl_last_hip_error() has the text */
+  MARL_HIP_ERROR = -4,     /* a launch failed; marl_last_hip_error() has the text */
+  MARL_OUT_OF_MEMORY = -5  /* a host allocation of the host-side helpers (balancer, page pool) failed */
 } marl_status;
 
 enum { MARL_OUT_BF16 = 0, MARL_OUT_F32 = 1 };
@@ -91,7 +92,9 @@ enum {
   MARL_CTR_PREFIX_CURSOR = 3,
   MARL_CTR_FLAGS = 4,            /* MARL_FLAG_* bits set by the kernels */
   MARL_CTR_NUM_LONG_SUFFIX_ITEMS = 5, /* suffix items of more than 128 tokens: they head the list */
-  MARL_CTR_SHORT_CURSOR = 6      /* work-queue cursor of the remaining (short) suffix items */
+  MARL_CTR_SHORT_CURSOR = 6,     /* work-queue cursor of the remaining (short) suffix items */
+  MARL_CTR_NUM_SHORT_PARTIAL_ITEMS = 7 /* suffix items of at most 128 tokens that belong to sequences with
+                                     several suffix chunks (the only short items that become partials) */
 };
 enum {
   MARL_FLAG_BAD_GROUP = 1,       /* a group_of_seq entry was outside [0, NG) */
@@ -135,7 +138,11 @@ int marl_workspace_bytes(const marl_attn_shape* shape, size_t* bytes);
  *                       entry are irrelevant, contents on exit are the work list and partials
  * q, k_pages, v_pages and out must be 16-byte aligned (MARL_INVALID_ARG otherwise): they are
  * accessed as 16-byte vectors.
- * Unused slots of a partly filled page and pages no table names are never read into a result.
+ * Unused slots of a partly filled page and pages no table names are never read into a result
+ * (they may hold anything, NaN included).  The values the call does use must be finite: q, and
+ * the keys and values of every token the lengths address.  With a NaN or an infinity among them
+ * the affected rows are unspecified (the attention kernels are compiled on the assumption that
+ * no NaN enters their floating-point arithmetic); the same holds for marl_prefill_attn.
  * Calls that share a workspace must be ordered on one stream.
  *
  * Work: a plan kernel builds the group->sequences CSR and two work lists (prefix items per
@@ -316,6 +323,8 @@ int marl_prefill_attn(const marl_prefill_shape* shape, void* workspace, size_t w
  * OR-ed, the caller zeroes it): the tokens of a group that do not fit its table row
  * (MARL_FLAG_LEN_CLAMPED), a group with an inconsistent q_start / q_pos0 entry
  * (MARL_FLAG_BAD_GROUP), a page id out of range (MARL_FLAG_BAD_PAGE).  Bit-exact data movement.
+ * k_new, k_pages and v_pages must be 16-byte aligned (MARL_INVALID_ARG otherwise): keys are
+ * copied, and whole value pages stored, as 16-byte vectors.
  */
 int marl_kv_write_prompt(const marl_prefill_shape* shape, const void* k_new, const void* v_new,
                          void* k_pages, void* v_pages, const int32_t* prefix_block_table,

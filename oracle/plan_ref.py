@@ -67,6 +67,16 @@ class PlanRef:
     def num_long_suffix_items(self) -> int:
         return sum(1 for it in self.suffix_items if it[2] - it[1] > SHORT_TOKENS)
 
+    @property
+    def num_short_partial_items(self) -> int:
+        """Suffix items of at most SHORT_TOKENS tokens whose sequence has several suffix chunks
+        (counted from the finished item list: how many items name each sequence)."""
+        per_seq = {}
+        for it in self.suffix_items:
+            per_seq[it[0]] = per_seq.get(it[0], 0) + 1
+        return sum(1 for it in self.suffix_items
+                   if it[2] - it[1] <= SHORT_TOKENS and per_seq[it[0]] >= 2)
+
 
 def build_plan(prefix_lens, suffix_lens, group_of_seq, Hq: int, Hkv: int, max_prefix_pages: int,
                max_suffix_pages: int, suffix_chunk: int = 0, prefix_chunk: int = 0) -> PlanRef:

@@ -20,7 +20,7 @@ VP = ctypes.c_void_p
 MARL_OUT_BF16, MARL_OUT_F32 = 0, 1
 STAGES = ("plan", "prefix", "suffix", "merge", "logprob", "logprob_finish")
 CTR_NUM_SUFFIX_ITEMS, CTR_NUM_PREFIX_ITEMS, CTR_SUFFIX_CURSOR, CTR_PREFIX_CURSOR, CTR_FLAGS, \
-    CTR_NUM_LONG_SUFFIX_ITEMS, CTR_SHORT_CURSOR = range(7)
+    CTR_NUM_LONG_SUFFIX_ITEMS, CTR_SHORT_CURSOR, CTR_NUM_SHORT_PARTIAL_ITEMS = range(8)
 FLAG_BAD_GROUP, FLAG_LEN_CLAMPED, FLAG_BAD_PAGE = 1, 2, 4
 
 
@@ -193,9 +193,41 @@ def _require_cuda(*tensors):
             raise ValueError("contiguous tensors required")
 
 
+def _require(t: Optional[torch.Tensor], name: str, dtype, shape=None):
+    """The kernels reinterpret raw bytes, so a wrong dtype (torch's default int64 for an index tensor,
+    float32 for bf16 data) or a wrong extent would give wrong results without any error: refuse it here.
+    `shape`: expected sizes, None entries are free."""
+    if t is None:
+        return
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if shape is not None:
+        if t.dim() != len(shape) or any(e is not None and int(g) != int(e) for g, e in zip(t.shape, shape)):
+            raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def _require_attn_operands(shape: AttnShape, q, k_pages, v_pages, prefix_block_table, suffix_block_table,
+                           prefix_lens, suffix_lens, group_of_seq, out):
+    NS, NG, Hq, Hkv = shape.num_seqs, shape.num_groups, shape.num_q_heads, shape.num_kv_heads
+    bf, i32 = torch.bfloat16, torch.int32
+    _require(q, "q", bf, (NS, Hq, 128))
+    _require(k_pages, "k_pages", bf, (shape.num_pages, Hkv, 16, 128))
+    _require(v_pages, "v_pages", bf, (shape.num_pages, Hkv, 128, 16))
+    if shape.max_prefix_pages > 0:
+        _require(prefix_block_table, "prefix_block_table", i32, (NG, shape.max_prefix_pages))
+    if shape.max_suffix_pages > 0:
+        _require(suffix_block_table, "suffix_block_table", i32, (NS, shape.max_suffix_pages))
+    _require(prefix_lens, "prefix_lens", i32, (NG,))
+    _require(suffix_lens, "suffix_lens", i32, (NS,))
+    _require(group_of_seq, "group_of_seq", i32, (NS,))
+    _require(out, "out", bf if shape.out_dtype == MARL_OUT_BF16 else torch.float32, (NS, Hq, 128))
+
+
 def marl_decode_attn(shape: AttnShape, workspace: torch.Tensor, q, k_pages, v_pages, prefix_block_table,
                      suffix_block_table, prefix_lens, suffix_lens, group_of_seq, scale: float,
                      out: torch.Tensor) -> torch.Tensor:
+    _require_attn_operands(shape, q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens,
+                           suffix_lens, group_of_seq, out)
     _require_cuda(workspace, q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens,
                   suffix_lens, group_of_seq, out)
     rc = load_library().marl_decode_attn(
@@ -215,6 +247,9 @@ def marl_decode_attn_static(shape: AttnShape, q, k_pages, v_pages, prefix_block_
     """marl_decode_attn on the library's own fixed workspace (no allocation in the call)."""
     _require_cuda(q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens, suffix_lens,
                   group_of_seq, out, flags)
+    _require_attn_operands(shape, q, k_pages, v_pages, prefix_block_table, suffix_block_table, prefix_lens,
+                           suffix_lens, group_of_seq, out)
+    _require(flags, "flags", torch.int32)
     rc = load_library().marl_decode_attn_static(
         ctypes.byref(shape), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(prefix_block_table),
         _ptr(suffix_block_table), _ptr(prefix_lens), _ptr(suffix_lens), _ptr(group_of_seq), float(scale),
@@ -225,6 +260,9 @@ def marl_decode_attn_static(shape: AttnShape, q, k_pages, v_pages, prefix_block_
 
 def marl_attn_plan(shape: AttnShape, workspace: torch.Tensor, prefix_lens, suffix_lens, group_of_seq):
     _require_cuda(workspace, prefix_lens, suffix_lens, group_of_seq)
+    _require(prefix_lens, "prefix_lens", torch.int32, (shape.num_groups,))
+    _require(suffix_lens, "suffix_lens", torch.int32, (shape.num_seqs,))
+    _require(group_of_seq, "group_of_seq", torch.int32, (shape.num_seqs,))
     rc = load_library().marl_attn_plan(ctypes.byref(shape), _ptr(workspace), workspace.numel(),
                                        _ptr(prefix_lens), _ptr(suffix_lens), _ptr(group_of_seq),
                                        _stream(workspace.device))
@@ -247,8 +285,11 @@ def marl_logprobs_workspace_bytes(rows: int, vocab: int) -> int:
 
 def marl_token_logprobs(logits: torch.Tensor, tokens: torch.Tensor, temperature: float, out: torch.Tensor,
                         workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    _require_cuda(logits, tokens, out, workspace)
+    _require(logits, "logits", torch.bfloat16, (None, None))
     rows, vocab = logits.shape
+    _require(tokens, "tokens", torch.int32, (rows,))
+    _require(out, "out", torch.float32, (rows,))
+    _require_cuda(logits, tokens, out, workspace)
     rc = load_library().marl_token_logprobs(
         _ptr(logits), _ptr(tokens), float(temperature), _ptr(out), rows, vocab, _ptr(workspace),
         0 if workspace is None else workspace.numel(), _stream(logits.device))
@@ -259,6 +300,14 @@ def marl_token_logprobs(logits: torch.Tensor, tokens: torch.Tensor, temperature:
 def marl_kv_append(shape: AttnShape, k_new, v_new, k_pages, v_pages, suffix_block_table, suffix_lens,
                    flags: Optional[torch.Tensor] = None):
     _require_cuda(k_new, v_new, k_pages, v_pages, suffix_block_table, suffix_lens, flags)
+    NS, Hkv = shape.num_seqs, shape.num_kv_heads
+    _require(k_new, "k_new", torch.bfloat16, (NS, Hkv, 128))
+    _require(v_new, "v_new", torch.bfloat16, (NS, Hkv, 128))
+    _require(k_pages, "k_pages", torch.bfloat16, (shape.num_pages, Hkv, 16, 128))
+    _require(v_pages, "v_pages", torch.bfloat16, (shape.num_pages, Hkv, 128, 16))
+    _require(suffix_block_table, "suffix_block_table", torch.int32, (NS, shape.max_suffix_pages))
+    _require(suffix_lens, "suffix_lens", torch.int32, (NS,))
+    _require(flags, "flags", torch.int32)
     rc = load_library().marl_kv_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_pages), _ptr(v_pages),
                                        _ptr(suffix_block_table), _ptr(suffix_lens), _ptr(flags),
                                        _stream(k_pages.device))
@@ -267,6 +316,11 @@ def marl_kv_append(shape: AttnShape, k_new, v_new, k_pages, v_pages, suffix_bloc
 
 def marl_kv_copy_pages(shape: AttnShape, k_pages, v_pages, src, dst, flags: Optional[torch.Tensor] = None):
     _require_cuda(k_pages, v_pages, src, dst, flags)
+    _require(k_pages, "k_pages", torch.bfloat16, (shape.num_pages, shape.num_kv_heads, 16, 128))
+    _require(v_pages, "v_pages", torch.bfloat16, (shape.num_pages, shape.num_kv_heads, 128, 16))
+    _require(src, "src", torch.int32, (None,))
+    _require(dst, "dst", torch.int32, (int(src.numel()),))
+    _require(flags, "flags", torch.int32)
     rc = load_library().marl_kv_copy_pages(ctypes.byref(shape), _ptr(k_pages), _ptr(v_pages), _ptr(src), _ptr(dst),
                                            int(src.numel()), _ptr(flags), _stream(k_pages.device))
     _check(rc, "marl_kv_copy_pages")
@@ -281,7 +335,11 @@ def marl_sample_workspace_bytes(rows: int, vocab: int) -> int:
 def marl_sample_tokens(logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, out_tokens: torch.Tensor,
                        out_logprobs: torch.Tensor, workspace: torch.Tensor):
     _require_cuda(logits, uniforms, out_tokens, out_logprobs, workspace)
+    _require(logits, "logits", torch.bfloat16, (None, None))
     rows, vocab = logits.shape
+    _require(uniforms, "uniforms", torch.float32, (rows,))
+    _require(out_tokens, "out_tokens", torch.int32, (rows,))
+    _require(out_logprobs, "out_logprobs", torch.float32, (rows,))
     rc = load_library().marl_sample_tokens(_ptr(logits), _ptr(uniforms), float(temperature), _ptr(out_tokens),
                                            _ptr(out_logprobs), rows, vocab, _ptr(workspace), workspace.numel(),
                                            _stream(logits.device))
@@ -292,7 +350,11 @@ def marl_sample_tokens(logits: torch.Tensor, uniforms: torch.Tensor, temperature
 def marl_sample_tokens_top_p(logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, top_p: float,
                              out_tokens: torch.Tensor, out_logprobs: torch.Tensor):
     _require_cuda(logits, uniforms, out_tokens, out_logprobs)
+    _require(logits, "logits", torch.bfloat16, (None, None))
     rows, vocab = logits.shape
+    _require(uniforms, "uniforms", torch.float32, (rows,))
+    _require(out_tokens, "out_tokens", torch.int32, (rows,))
+    _require(out_logprobs, "out_logprobs", torch.float32, (rows,))
     rc = load_library().marl_sample_tokens_top_p(_ptr(logits), _ptr(uniforms), float(temperature), float(top_p),
                                                  _ptr(out_tokens), _ptr(out_logprobs), rows, vocab,
                                                  _stream(logits.device))
@@ -303,6 +365,10 @@ def marl_sample_tokens_top_p(logits: torch.Tensor, uniforms: torch.Tensor, tempe
 def marl_grpo_advantages(rewards: torch.Tensor, group_start: torch.Tensor, group_seqs: torch.Tensor, eps: float,
                          out: torch.Tensor):
     _require_cuda(rewards, group_start, group_seqs, out)
+    _require(rewards, "rewards", torch.float32, (None,))
+    _require(group_start, "group_start", torch.int32, (None,))
+    _require(group_seqs, "group_seqs", torch.int32, (None,))
+    _require(out, "out", torch.float32, (int(rewards.numel()),))
     rc = load_library().marl_grpo_advantages(_ptr(rewards), _ptr(group_start), _ptr(group_seqs),
                                              int(group_start.numel()) - 1, float(eps), _ptr(out),
                                              _stream(rewards.device))
@@ -326,6 +392,14 @@ def marl_prefill_workspace_bytes(shape: PrefillShape) -> int:
 def marl_prefill_attn(shape: PrefillShape, workspace, q, k_pages, v_pages, prefix_block_table, q_start, q_pos0,
                       scale: float, out):
     _require_cuda(workspace, q, k_pages, v_pages, prefix_block_table, q_start, q_pos0, out)
+    NT, NG, Hq, Hkv = shape.num_tokens, shape.num_groups, shape.num_q_heads, shape.num_kv_heads
+    _require(q, "q", torch.bfloat16, (NT, Hq, 128))
+    _require(k_pages, "k_pages", torch.bfloat16, (shape.num_pages, Hkv, 16, 128))
+    _require(v_pages, "v_pages", torch.bfloat16, (shape.num_pages, Hkv, 128, 16))
+    _require(prefix_block_table, "prefix_block_table", torch.int32, (NG, shape.max_prefix_pages))
+    _require(q_start, "q_start", torch.int32, (NG + 1,))
+    _require(q_pos0, "q_pos0", torch.int32, (NG,))
+    _require(out, "out", torch.bfloat16 if shape.out_dtype == MARL_OUT_BF16 else torch.float32, (NT, Hq, 128))
     rc = load_library().marl_prefill_attn(ctypes.byref(shape), _ptr(workspace), workspace.numel(), _ptr(q),
                                           _ptr(k_pages), _ptr(v_pages), _ptr(prefix_block_table), _ptr(q_start),
                                           _ptr(q_pos0), float(scale), _ptr(out), _stream(q.device))
@@ -336,6 +410,15 @@ def marl_prefill_attn(shape: PrefillShape, workspace, q, k_pages, v_pages, prefi
 def marl_kv_write_prompt(shape: PrefillShape, k_new, v_new, k_pages, v_pages, prefix_block_table, q_start, q_pos0,
                          flags=None):
     _require_cuda(k_new, v_new, k_pages, v_pages, prefix_block_table, q_start, q_pos0, flags)
+    NT, NG, Hkv = shape.num_tokens, shape.num_groups, shape.num_kv_heads
+    _require(k_new, "k_new", torch.bfloat16, (NT, Hkv, 128))
+    _require(v_new, "v_new", torch.bfloat16, (NT, Hkv, 128))
+    _require(k_pages, "k_pages", torch.bfloat16, (shape.num_pages, Hkv, 16, 128))
+    _require(v_pages, "v_pages", torch.bfloat16, (shape.num_pages, Hkv, 128, 16))
+    _require(prefix_block_table, "prefix_block_table", torch.int32, (NG, shape.max_prefix_pages))
+    _require(q_start, "q_start", torch.int32, (NG + 1,))
+    _require(q_pos0, "q_pos0", torch.int32, (NG,))
+    _require(flags, "flags", torch.int32)
     rc = load_library().marl_kv_write_prompt(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(k_pages),
                                              _ptr(v_pages), _ptr(prefix_block_table), _ptr(q_start), _ptr(q_pos0),
                                              _ptr(flags) if flags is not None else None, _stream(k_new.device))

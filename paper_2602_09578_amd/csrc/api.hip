@@ -294,6 +294,7 @@ const char* marl_status_string(int status) {
     case MARL_UNSUPPORTED: return "unsupported shape or option";
     case MARL_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MARL_HIP_ERROR: return "HIP error";
+    case MARL_OUT_OF_MEMORY: return "out of host memory";
     default: return "unknown status";
   }
 }
@@ -669,8 +670,8 @@ int marl_kv_write_prompt(const marl_prefill_shape* shape, const void* k_new, con
   if (shape->max_prefix_pages < 1) return MARL_INVALID_ARG;
   // one workgroup per (group, KV head, table column)
   if ((long)shape->num_groups * shape->num_kv_heads * shape->max_prefix_pages >= (1L << 31)) return MARL_UNSUPPORTED;
-  if (reinterpret_cast<uintptr_t>(k_new) % 16 != 0 || reinterpret_cast<uintptr_t>(k_pages) % 16 != 0)
-    return MARL_INVALID_ARG;
+  // keys are copied, and whole value pages stored, as 16-byte vectors
+  if (!aligned16(k_new) || !aligned16(k_pages) || !aligned16(v_pages)) return MARL_INVALID_ARG;
   marl::PrefillArgs a;
   fill_prefill_args(shape, a);
   a.k_new = static_cast<const uint16_t*>(k_new);

@@ -449,11 +449,18 @@ __device__ __forceinline__ void short_suffix_items(const AttnArgs& a, int& bad_p
 // ahead (48 KB in flight per workgroup).  No cross-wave reduction is needed.
 //
 // LDS tile of one step (16 KB): K as 32 token rows of 256 B, the 16-byte chunk index of
-// row tau XOR-ed with (tau&3)|((tau>>1)&4) so that the 8 lanes of an operand read hit 8
-// different 16-byte bank groups; V as [page][channel][2 halves of 8 slots], the 16-byte
-// unit index u XOR-ed with (u>>3)&1 for the same reason.
+// row tau XOR-ed with a 4-bit key made of bits 0, 1, 3, 4 of tau: the 16 rows that the 16 lanes
+// of one operand read touch differ in exactly those bits, so they hit 16 different 16-byte bank
+// groups (measured: 4.1 cycles per wave instruction per CU against 7.3 with a 3-bit key, 4.0 for
+// a plain linear read); V as [page][channel][2 halves of 8 slots], the 16-byte unit index u
+// XOR-ed with (u>>3)&1 for the same reason.
 // ---------------------------------------------------------------------------------------
 constexpr int kStepBytes = 2 * kBlockTok * kD * 2;   // K + V of one 32-token step
+// the pipelined prefix item rescales its accumulators only when a row's score maximum exceeds the
+// running reference by more than this (log2 units): weights then stay below 2^kRescaleSlack
+constexpr float kRescaleSlack = 8.0f;
+// s_waitcnt immediate (gfx9 encoding): vector-memory counter <= vm, LDS/scalar counter <= lgkm
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 0xf) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 0xf) << 8); }
 struct PrefixLds {
   __attribute__((aligned(16))) char buf[3][kStepBytes];
 };
@@ -537,10 +544,11 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
     second_page[k] = region & 1;
     const bool is_v = region >> 1;
     src_base[k] = reinterpret_cast<const char*>(is_v ? a.v_pages : a.k_pages) + (size_t)kvh * (kPage * kD * 2) + w * 16;
-    // K rows of page 1 are tau = 16 + slot: the swizzle key (tau&3)|((tau>>1)&4) is that of slot
+    // K rows of page 1 are tau = 16 + slot; swizzle key of row tau: bits 0, 1, 3, 4 of tau
     const int slot = w >> 4;
+    const int key = ((region & 1) << 3) | ((slot >> 3) << 2) | (slot & 3);
     lds_off[k] = is_v ? 2 * kBlockTok * kD + (region & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
-                      : ((region & 1) * 16 + slot) * 256 + (((w & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)) << 4);
+                      : ((region & 1) * 16 + slot) * 256 + (((w & 15) ^ key) << 4);
   }
   // The loads are unconditional (a step past the end re-reads 16 valid bytes that are never
   // used) so that every wait in the loop knows exactly how many younger loads are in flight.
@@ -554,7 +562,7 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) *reinterpret_cast<u32x4*>(buf + lds_off[k]) = st[k];
   };
-  // operand reads: K row tau = 8*(i/4) + 4T + i%4, whose swizzle key is i & 7
+  // operand reads: K row tau = 8*(i/4) + 4T + i%4, whose swizzle key is i
   const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
   const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
 
@@ -568,7 +576,7 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
       for (int T = 0; T < 2; ++T)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-          kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ (i & 7)) << 4));
+          kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ i) << 4));
 #pragma unroll
       for (int qt = 0; qt < MTW; ++qt) {
         pb[qt] = u32x4{0u, 0u, 0u, 0u};
@@ -683,6 +691,339 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   }
 }
 
+// Prefix item, software-pipelined.  Data path as before (global memory -> staging registers, three
+// steps ahead -> LDS ring of three step buffers -> operand registers); what changes is the order
+// inside an iteration, chosen so that no LDS read is waited for where it is issued and so that the
+// K and V operand registers share one set of 32 registers:
+//   iteration n:  loads of step n+3 -> staging registers
+//                 output products of step n-1, first half  (its V and weights are in registers)
+//                 read K(n), first half   (into the V registers the first half has released)
+//                 output products of step n-1, second half
+//                 read K(n), second half
+//                 score products of step n (first the half whose K has arrived)
+//                 read V(n)               (into the K registers)
+//                 softmax of step n       (covers the V read; leaves the bf16 weights)
+//                 step n+1: staging registers -> LDS; workgroup barrier
+// The hot loop has no per-tile branch (the number of active tiles is a template parameter), the
+// ragged last step is peeled, and accumulators are rescaled only when a row's score maximum exceeds
+// the running reference by more than 2^tau (weights stay below 2^tau), right before the output
+// products that need it, so that branch is taken a handful of times per chunk.  Row sums come out
+// of the matrix core (a product with an all-ones tile), from the same bf16-rounded weights that
+// multiply V.
+template <int MTW, int NW>
+__device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const int4 it, const int kvh,
+                                               PrefixLds& lds, int& bad_page) {
+  constexpr int kQBlock = 32 * NW;
+  constexpr int kLoads = 1024 / (NW * 64);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i = lane & 15, j = lane >> 4;
+  const int g = it.x, tok_begin = it.y, tok_end = it.z, row_begin = it.w;
+  const int32_t* table_row = a.prefix_table + (size_t)g * a.max_pp;
+  const int nsteps = (tok_end - tok_begin + kBlockTok - 1) / kBlockTok;
+  const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
+
+  // Page ids of step n (wave-uniform scalar loads); -1 for a step past the end.
+  auto load_ids = [&](int n, int& p0, int& p1) {
+    p0 = -1;
+    p1 = -1;
+    if (n < nsteps) {
+      const int t = tok_begin + n * kBlockTok;
+      p0 = ld_uniform(table_row + (t >> 4));
+      p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
+      if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
+      if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
+    }
+  };
+  // A step is 1024 16-byte vectors: K of page 0, K of page 1, V of page 0, V of page 1 (256 each,
+  // contiguous in memory).  Thread tid fetches vectors tid + k * threads, k < kLoads.  Of a page's
+  // 256 vectors, vector w is slot w/16, chunk w%16 of K, or 16-byte unit w of V.
+  // LDS tile: K as 32 token rows of 256 B, the 16-byte chunk index XOR-ed with a 4-bit key made of
+  // bits 0, 1, 3, 4 of the row (the 16 rows one operand read touches differ exactly in those bits,
+  // so its 16 lanes hit 16 different bank groups); V as [page][channel][2 halves of 8 slots], the
+  // unit index u XOR-ed with (u >> 3) & 1.
+  // Which of the four regions a load belongs to is the same for a whole wave (wave-uniform), so a
+  // page's base address is scalar arithmetic and every lane adds the same 32-bit offset for all loads.
+  static_assert(NW % 4 == 0, "a wave's 64 vectors must lie in one 256-vector region");
+  const int w = tid & 255;
+  const uint32_t lane_off = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)w * 16;
+  const int sl = w >> 4;
+  const int lds_k = sl * 256 + (((w & 15) ^ (((sl >> 3) << 2) | (sl & 3))) << 4);   // page 0; page 1: + 4096, chunk ^ 8
+  const int lds_v = 2 * kBlockTok * kD + ((w ^ ((w >> 3) & 1)) << 4);              // page 0; page 1: + 4096
+  auto region_of = [&](int k) { return k * (NW / 4) + (wave >> 2); };               // wave-uniform
+  auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int region = region_of(k);
+      // a step past the end re-reads the start of the key array (bytes nobody uses, from cache), so
+      // that the loads stay unconditional and every wait knows how many are in flight
+      const char* base = reinterpret_cast<const char*>((region >> 1) && p0 >= 0 ? a.v_pages : a.k_pages) +
+                         (p0 >= 0 ? (size_t)((region & 1) ? p1 : p0) * page_bytes : (size_t)0);
+      st[k] = ld_stream(base + (p0 >= 0 ? lane_off : 0u));
+    }
+  };
+  auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int region = region_of(k);
+      const int off = (region >> 1) ? lds_v + (region & 1) * 4096 : (lds_k + (region & 1) * 4096) ^ ((region & 1) << 7);
+      *reinterpret_cast<u32x4*>(buf + off) = st[k];
+    }
+  };
+  // the first three steps are requested before anything else of the item: the chain of dependent
+  // loads that leads to the query rows then runs while they are in flight
+  u32x4 st[3][kLoads];   // steps in flight: three register stages
+  int p0, p1;
+#pragma unroll
+  for (int s0 = 0; s0 < 3; ++s0) {
+    load_ids(s0, p0, p1);
+    issue(p0, p1, st[s0]);
+  }
+  load_ids(3, p0, p1);
+
+  const int gstart = a.group_start[g];
+  const int nrows = a.group_count[g] * a.R;
+  const float sc = fmaxf(fabsf(a.scale) * 1.44269504088896340736f, 1e-30f);
+  const uint32_t sign_flip = a.scale < 0.f ? 0x80008000u : 0u;
+  const int nslot = a.NCp + a.NCs;
+  const int slot = tok_begin / a.Cp;
+  const int tiles_total = (min(kQBlock, nrows - row_begin) + 15) >> 4;
+  const int nt = max(0, min(MTW, (tiles_total - wave + NW - 1) / NW));   // wave-uniform
+  int row_index[MTW];
+  u32x4 qreg[MTW][4];
+#pragma unroll
+  for (int qt = 0; qt < MTW; ++qt) {
+    const int rho = row_begin + (qt * NW + wave) * 16 + i;
+    int idx = -1;
+    if (rho < nrows && (qt * NW + wave) * 16 < kQBlock)
+      idx = a.group_seqs[gstart + rho / a.R] * a.Hq + kvh * a.R + rho % a.R;
+    row_index[qt] = idx;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (idx >= 0) {
+        v = *reinterpret_cast<const u32x4*>(a.q + (size_t)idx * kD + (4 * kk + j) * 8);
+        v ^= sign_flip;
+      }
+      qreg[qt][kk] = v;
+    }
+  }
+  f32x4 acc[MTW][8];
+  f32x4 lacc[MTW];          // row sums accumulated by the matrix core (all four elements equal)
+  float m_run[MTW];
+#pragma unroll
+  for (int qt = 0; qt < MTW; ++qt) {
+    m_run[qt] = -INFINITY;
+    lacc[qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) acc[qt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
+  const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
+  auto read_k_half = [&](const char* buf, int T, u32x4 (&kr)[4]) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      kr[kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ i) << 4));
+  };
+  auto read_v_half = [&](const char* buf, int h, u32x4 (&vr)[4]) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int u = 2 * (16 * (4 * h + c) + i) + (j & 1);
+      vr[c] = *reinterpret_cast<const u32x4*>(buf + v_rd + ((u ^ ((i >> 2) & 1)) << 4));
+    }
+  };
+  const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+
+  auto run = [&](auto nt_tag) {
+    constexpr int NTraw = decltype(nt_tag)::value;
+    constexpr int NT = NTraw > 0 ? NTraw : 1;   // (no zero-length arrays; a wave without tiles only moves data)
+    // xa / xb: the two halves of the operand registers: V(n-1) channel tiles 0-3 / 4-7 at the top of
+    // iteration n, then K(n) token half 0 / 1, then V(n)
+    u32x4 xa[4], xb[4], pb[NT];
+    float alpha_pending[NT];
+    bool rescale_pending = false;   // wave-uniform
+
+    auto rescale_if_pending = [&]() {
+      if (rescale_pending) {
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) {
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= alpha_pending[qt];
+          lacc[qt] *= alpha_pending[qt];
+        }
+      }
+    };
+    auto output_half = [&](int h, const u32x4 (&vr)[4]) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) acc[qt][4 * h + c] = mfma_16x16x32(vr[c], pb[qt], acc[qt][4 * h + c]);
+      if (h == 0) {
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) lacc[qt] = mfma_16x16x32(ones, pb[qt], lacc[qt]);
+      }
+    };
+    auto scores_half = [&](int T, const u32x4 (&kr)[4], f32x4 (&s)[NT][2]) {
+#pragma unroll
+      for (int qt = 0; qt < NT; ++qt) s[qt][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) s[qt][T] = mfma_16x16x32(kr[kk], qreg[qt][kk], s[qt][T]);
+    };
+    // softmax of step n from its scores: leaves the bf16 weights in pb (and masks, in the ragged last
+    // step, the scores and the value slots no token owns)
+    auto softmax = [&](auto last_tag, int n, f32x4 (&s)[NT][2]) {
+      constexpr bool kLast = decltype(last_tag)::value;
+      if constexpr (kLast) {
+        const int t0 = tok_begin + n * kBlockTok;
+        if (t0 + kBlockTok > tok_end) {   // wave-uniform: the ragged end of the chunk
+#pragma unroll
+          for (int qt = 0; qt < NT; ++qt)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (t0 + 8 * j + e >= tok_end) s[qt][0][e] = -INFINITY;
+              if (t0 + 8 * j + 4 + e >= tok_end) s[qt][1][e] = -INFINITY;
+            }
+          // value slots no token owns may hold anything (NaN included): zero them
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const int tok = t0 + 8 * j + 2 * d;
+            const uint32_t mask = (tok < tok_end ? 0x0000ffffu : 0u) | (tok + 1 < tok_end ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              xa[c][d] &= mask;
+              xb[c][d] &= mask;
+            }
+          }
+        }
+      }
+      float mx[NT];
+      bool moved = false;
+#pragma unroll
+      for (int qt = 0; qt < NT; ++qt) {
+        const f32x4 s0 = s[qt][0], s1 = s[qt][1];
+        const float m8 = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                               fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+        mx[qt] = rows_allreduce_max(m8) * sc;
+        moved |= mx[qt] > m_run[qt] + kRescaleSlack;
+      }
+      rescale_pending = __builtin_amdgcn_ballot_w64(moved) != 0;   // wave-uniform; rare after a chunk's first step
+      if (rescale_pending) {
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) {
+          const float m_new = mx[qt] > m_run[qt] + kRescaleSlack ? mx[qt] : m_run[qt];
+          alpha_pending[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);   // 1 where the row did not move
+          m_run[qt] = m_new;
+        }
+      }
+#pragma unroll
+      for (int qt = 0; qt < NT; ++qt) {
+        float p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][0][e], sc, -m_run[qt]));
+          p[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][1][e], sc, -m_run[qt]));
+        }
+        pb[qt] = u32x4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+      }
+    };
+    // iteration n (n % 3 == PH): buf[PH] holds step n; the staging set PH takes the loads of step
+    // n+3; set PH+1 (step n+1) goes to buf[PH+1]
+    auto iteration = [&](auto first_tag, auto last_tag, auto phase_tag, int n) {
+      constexpr bool kFirst = decltype(first_tag)::value;
+      constexpr int PH = decltype(phase_tag)::value;
+      const char* bufr = lds.buf[PH];
+      char* bufw = lds.buf[(PH + 1) % 3];
+      issue(p0, p1, st[PH]);
+      load_ids(n + 4, p0, p1);
+      if constexpr (NTraw > 0) {
+        f32x4 s[NT][2];
+        if constexpr (!kFirst) {
+          rescale_if_pending();
+          output_half(0, xa);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        read_k_half(bufr, 0, xa);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (!kFirst) {
+          output_half(1, xb);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        read_k_half(bufr, 1, xb);
+        __builtin_amdgcn_sched_barrier(0);
+        scores_half(0, xa, s);
+        __builtin_amdgcn_sched_barrier(0);
+        scores_half(1, xb, s);
+        __builtin_amdgcn_sched_barrier(0);
+        read_v_half(bufr, 0, xa);
+        read_v_half(bufr, 1, xb);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(last_tag)::value)
+          __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));   // the ragged step masks the values it has just read
+        softmax(last_tag, n, s);
+      }
+      // step n+1 goes from its staging registers to LDS once it has landed (the loads of the two
+      // younger steps stay in flight), then the barrier
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * kLoads, 15));
+      stage_to_lds(st[(PH + 1) % 3], bufw);
+      __syncthreads();
+    };
+    const std::true_type yes{};
+    const std::false_type no{};
+    using P0 = std::integral_constant<int, 0>;
+
+    // step 0 into LDS
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * kLoads, 15));
+    stage_to_lds(st[0], lds.buf[0]);
+    __syncthreads();
+    if (nsteps == 1) {
+      iteration(yes, yes, P0{}, 0);
+    } else {
+      iteration(yes, no, P0{}, 0);
+      int n = 1;
+      // the steps that are neither first nor last, phases 1, 2, ..., 3-1, 0 in turn
+      auto middle = [&](auto ph) {
+        if (n + 1 >= nsteps) return false;
+        iteration(no, no, ph, n);
+        ++n;
+        return true;
+      };
+      auto cycle = [&](auto... ph) { return (middle(ph) && ...); };
+      while (n + 1 < nsteps) {
+        cycle(std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, P0{});
+      }
+      const int last = nsteps - 1;
+      const int lp = last % 3;
+      if (lp == 0) iteration(no, yes, P0{}, last);
+      else if (lp == 1) iteration(no, yes, std::integral_constant<int, 1>{}, last);
+      else iteration(no, yes, std::integral_constant<int, 2>{}, last);
+    }
+    if constexpr (NTraw > 0) {   // the last step's output products
+      rescale_if_pending();
+      output_half(0, xa);
+      output_half(1, xb);
+    }
+    // every wave has passed a barrier since its last LDS read: the next item may refill the ring
+  };
+  if (nt == MTW) run(std::integral_constant<int, MTW>{});
+  else if (MTW == 2 && nt == 1) run(std::integral_constant<int, 1>{});
+  else run(std::integral_constant<int, 0>{});
+
+#pragma unroll
+  for (int qt = 0; qt < MTW; ++qt) {
+    if (row_index[qt] >= 0) {
+      const size_t ps = (size_t)row_index[qt] * nslot + slot;
+      float* dst = a.partial_o + ps * kD + 4 * j;
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) *reinterpret_cast<f32x4*>(dst + 16 * ct) = acc[qt][ct];
+      if (j == 0) a.partial_ml[ps] = make_float2(m_run[qt], lacc[qt][0]);
+    }
+  }
+}
+
 template <int NW>
 __device__ __forceinline__ void prefix_kernel_body(const AttnArgs& a) {
   __shared__ PrefixLds lds;
@@ -692,7 +1033,9 @@ __device__ __forceinline__ void prefix_kernel_body(const AttnArgs& a) {
   // The short suffix items go first: each round is a chain of dependent memory accesses with
   // little data, which is cheap while every workgroup has other work to overlap it with and
   // expensive at the tail of a kernel, where only a few workgroups are left.
-  short_suffix_items<false>(a, bad_page);
+  // (skipped when the plan found no such item: the scan of the short entries is a chain of
+  // dependent loads at the very start of the kernel)
+  if (a.counters[MARL_CTR_NUM_SHORT_PARTIAL_ITEMS] > 0) short_suffix_items<false>(a, bad_page);
   __syncthreads();
   for (bool first = true;; first = false) {   // first item = block index, as in the suffix kernel
     int qi = blockIdx.x;
@@ -706,8 +1049,15 @@ __device__ __forceinline__ void prefix_kernel_body(const AttnArgs& a) {
     const int4 it = a.prefix_items[qi / a.Hkv];
     const int kvh = qi % a.Hkv;
     const int rows = min(32 * NW, a.group_count[it.x] * a.R - it.w);
-    if (rows <= 16 * NW) prefix_item<1, NW>(a, it, kvh, lds, bad_page);   // workgroup-uniform
-    else prefix_item<2, NW>(a, it, kvh, lds, bad_page);
+    // (workgroup-uniform)  The 8-wave shape, whose items are bound by the matrix and vector units,
+    // runs the pipelined item; the 4-wave shape, bound by HBM, the plain one (measured faster there).
+    if constexpr (NW == 8) {
+      if (rows <= 16 * NW) prefix_item_pipelined<1, NW>(a, it, kvh, lds, bad_page);
+      else prefix_item_pipelined<2, NW>(a, it, kvh, lds, bad_page);
+    } else {
+      if (rows <= 16 * NW) prefix_item<1, NW>(a, it, kvh, lds, bad_page);
+      else prefix_item<2, NW>(a, it, kvh, lds, bad_page);
+    }
   }
   if (bad_page) atomicOr(&a.counters[MARL_CTR_FLAGS], MARL_FLAG_BAD_PAGE);
 }

@@ -17,6 +17,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "marl_decode.h"
@@ -99,7 +100,7 @@ struct marl_balancer {
   marl_balancer_config cfg;
   int64_t now = 0, completed = 0, migrations = 0;
   std::vector<Request> requests;                 // by submission order
-  std::vector<int32_t> slot_of_id;               // request id -> index in `requests`, -1 if unknown
+  std::unordered_map<int32_t, int32_t> slot_of_id;   // request id -> index in `requests` (ids may be sparse)
   std::vector<std::vector<int32_t>> lists;       // per instance: indices into `requests`, FIFO
   std::vector<int32_t> owner, target;            // per instance: agent, or -1 while in transit
   std::vector<int64_t> arrive;                   // per instance in transit: step at which it joins `target`
@@ -121,6 +122,18 @@ struct marl_balancer {
   }
 };
 
+// No exception may cross the C boundary: a failed host allocation becomes a status code.
+template <class F>
+int guarded(F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return MARL_OUT_OF_MEMORY;
+  } catch (...) {
+    return MARL_INVALID_ARG;
+  }
+}
+
 extern "C" {
 
 int marl_balancer_create(const marl_balancer_config* cfg, const int32_t* instances_per_agent,
@@ -136,20 +149,27 @@ int marl_balancer_create(const marl_balancer_config* cfg, const int32_t* instanc
     if (total > (1 << 24)) return MARL_UNSUPPORTED;
   }
   marl_balancer* b = new (std::nothrow) marl_balancer;
-  if (!b) return MARL_INVALID_ARG;
-  b->cfg = *cfg;
-  b->lists.resize(total);
-  b->owner.resize(total);
-  b->target.assign(total, -1);
-  b->arrive.assign(total, 0);
-  b->heaps.reserve(cfg->num_agents);
-  int32_t inst = 0;
-  for (int a = 0; a < cfg->num_agents; ++a) {
-    b->heaps.emplace_back(&b->lists);
-    for (int k = 0; k < instances_per_agent[a]; ++k, ++inst) {
-      b->owner[inst] = a;
-      b->heaps[a].push(inst);
+  if (!b) return MARL_OUT_OF_MEMORY;
+  const int rc = guarded([&] {
+    b->cfg = *cfg;
+    b->lists.resize(total);
+    b->owner.resize(total);
+    b->target.assign(total, -1);
+    b->arrive.assign(total, 0);
+    b->heaps.reserve(cfg->num_agents);
+    int32_t inst = 0;
+    for (int a = 0; a < cfg->num_agents; ++a) {
+      b->heaps.emplace_back(&b->lists);
+      for (int k = 0; k < instances_per_agent[a]; ++k, ++inst) {
+        b->owner[inst] = a;
+        b->heaps[a].push(inst);
+      }
     }
+    return (int)MARL_OK;
+  });
+  if (rc != MARL_OK) {
+    delete b;
+    return rc;
   }
   *out = b;
   return MARL_OK;
@@ -160,17 +180,19 @@ void marl_balancer_destroy(marl_balancer* b) { delete b; }
 int marl_balancer_submit(marl_balancer* b, int32_t agent, int32_t request_id, int32_t gen_len,
                          int32_t* instance) {
   if (!b || agent < 0 || agent >= b->cfg.num_agents || request_id < 0 || gen_len < 1) return MARL_INVALID_ARG;
-  if ((size_t)request_id >= b->slot_of_id.size()) b->slot_of_id.resize((size_t)request_id + 1, -1);
-  if (b->slot_of_id[request_id] >= 0) return MARL_INVALID_ARG;   // ids are unique
-  b->slot_of_id[request_id] = (int32_t)b->requests.size();
-  b->requests.push_back(Request{request_id, agent, gen_len, 0, -1, -1});
-  const int32_t inst = b->dispatch((int32_t)b->requests.size() - 1);
-  if (instance) *instance = inst;
-  return MARL_OK;
+  if (b->requests.size() >= (size_t)INT32_MAX) return MARL_UNSUPPORTED;
+  return guarded([&] {
+    if (!b->slot_of_id.emplace(request_id, (int32_t)b->requests.size()).second) return (int)MARL_INVALID_ARG;   // ids are unique
+    b->requests.push_back(Request{request_id, agent, gen_len, 0, -1, -1});
+    const int32_t inst = b->dispatch((int32_t)b->requests.size() - 1);
+    if (instance) *instance = inst;
+    return (int)MARL_OK;
+  });
 }
 
 int marl_balancer_step(marl_balancer* b, marl_balancer_stats* stats) {
   if (!b) return MARL_INVALID_ARG;
+  return guarded([&] {
   const int32_t I = (int32_t)b->lists.size(), A = b->cfg.num_agents, slots = b->cfg.slots_per_instance;
   // 1. instances whose weight transfer has finished join their new agent
   for (int32_t inst = 0; inst < I; ++inst)
@@ -237,7 +259,8 @@ int marl_balancer_step(marl_balancer* b, marl_balancer_stats* stats) {
     stats->submitted = (int64_t)b->requests.size();
     stats->migrations = b->migrations;
   }
-  return MARL_OK;
+  return (int)MARL_OK;
+  });
 }
 
 int marl_balancer_agent_state(const marl_balancer* b, int32_t agent, int32_t* active_instances,
@@ -273,9 +296,10 @@ int marl_balancer_instance_batch(const marl_balancer* b, int32_t instance, int32
 
 int marl_balancer_request_state(const marl_balancer* b, int32_t request_id, int32_t* instance,
                                 int32_t* generated, int64_t* done_step) {
-  if (!b || request_id < 0 || (size_t)request_id >= b->slot_of_id.size() || b->slot_of_id[request_id] < 0)
-    return MARL_INVALID_ARG;
-  const Request& r = b->requests[b->slot_of_id[request_id]];
+  if (!b || request_id < 0) return MARL_INVALID_ARG;
+  const auto it = b->slot_of_id.find(request_id);
+  if (it == b->slot_of_id.end()) return MARL_INVALID_ARG;
+  const Request& r = b->requests[it->second];
   if (instance) *instance = r.instance;
   if (generated) *generated = r.generated;
   if (done_step) *done_step = r.done_step;

@@ -44,10 +44,17 @@ extern "C" {
 int marl_page_pool_create(int32_t num_pages, marl_page_pool** out) {
   if (num_pages < 1 || !out) return MARL_INVALID_ARG;
   marl_page_pool* p = new (std::nothrow) marl_page_pool;
-  if (!p) return MARL_INVALID_ARG;
-  p->count.assign(num_pages, 0);
-  p->scratch.assign(num_pages, 0);
-  p->free_stack.resize(num_pages);
+  if (!p) return MARL_OUT_OF_MEMORY;
+  // the only host allocations of a pool's life (the free stack never outgrows num_pages entries);
+  // a failure here must not cross the C boundary as an exception
+  try {
+    p->count.assign(num_pages, 0);
+    p->scratch.assign(num_pages, 0);
+    p->free_stack.resize(num_pages);
+  } catch (...) {
+    delete p;
+    return MARL_OUT_OF_MEMORY;
+  }
   for (int32_t i = 0; i < num_pages; ++i) p->free_stack[i] = num_pages - 1 - i;   // pops 0, 1, 2, ...
   *out = p;
   return MARL_OK;

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   __shared__ int hist_s[kNumClasses];
   __shared__ int hist_p[kNumClasses];
   __shared__ int tmp[17];
-  __shared__ int n_long_items;
+  __shared__ int n_long_items, n_short_partial_items;
   const int tid = threadIdx.x;
   const int Cs = a.Cs, Cp = a.Cp, R = a.R, QB = a.qblock_rows;
   const int ncls_s = Cs / 32, ncls_p = Cp / 32;
@@ -85,14 +85,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
   for (int i = tid; i < kNumClasses; i += kPlanThreads) { hist_s[i] = 0; hist_p[i] = 0; }
   for (int g = tid; g < a.NG; g += kPlanThreads) a.group_count[g] = 0;
   if (tid < 64) a.counters[tid] = 0;
-  if (tid == 0) n_long_items = 0;
+  if (tid == 0) { n_long_items = 0; n_short_partial_items = 0; }
   __threadfence();
   __syncthreads();
 
   // sequences: rank inside the group, histogram of suffix items by cost class
   // (full chunks and long items: counted per thread, added once per wave, since same-address LDS
   // atomics run one lane at a time)
-  int nfull_mine = 0, nlong_mine = 0;
+  int nfull_mine = 0, nlong_mine = 0, nshort_partial_mine = 0;
   for (int s = tid; s < a.NS; s += kPlanThreads) {
     const int g = a.group_of_seq[s];
     int rank = -1;
@@ -104,12 +104,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
     nfull_mine += nfull;
     if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
     nlong_mine += (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
+    // short items (at most kShortTokens tokens) of sequences with several suffix chunks: they become partials
+    if (nfull + (tail > 0) >= 2)
+      nshort_partial_mine += (Cs <= kShortTokens ? nfull : 0) + ((tail > 0 && tail <= kShortTokens) ? 1 : 0);
   }
   nfull_mine = wave_sum(nfull_mine);
   nlong_mine = wave_sum(nlong_mine);
+  nshort_partial_mine = wave_sum(nshort_partial_mine);
   if (lane_id() == 0) {
     if (nfull_mine) atomicAdd(&hist_s[0], nfull_mine);
     if (nlong_mine) atomicAdd(&n_long_items, nlong_mine);
+    if (nshort_partial_mine) atomicAdd(&n_short_partial_items, nshort_partial_mine);
   }
   __threadfence();
   __syncthreads();
@@ -201,6 +206,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(AttnArgs a) {
     a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] = n_suffix_items;
     a.counters[MARL_CTR_NUM_PREFIX_ITEMS] = n_prefix_items;
     a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] = n_long_items;
+    a.counters[MARL_CTR_NUM_SHORT_PARTIAL_ITEMS] = n_short_partial_items;
   }
 }
 
@@ -224,7 +230,7 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
   __shared__ int hist_s[kSmallMaxClasses];
   __shared__ int hist_p[kSmallMaxClasses];
   __shared__ int tmp[17];
-  __shared__ int n_long_items;
+  __shared__ int n_long_items, n_short_partial_items;
   // clamped prefix lengths, where there is room for them (else they are re-read from global memory)
   constexpr bool kPrefixLensInLds = kSmallMaxGroups <= 2048;
   __shared__ int prefix_len[kPrefixLensInLds ? kSmallMaxGroups : 1];
@@ -262,13 +268,13 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
   }
   for (int i = tid; i < kSmallMaxGroups; i += kPlanThreads) cnt[i] = 0;
   for (int i = tid; i < kSmallMaxClasses; i += kPlanThreads) { hist_s[i] = 0; hist_p[i] = 0; }
-  if (tid == 0) n_long_items = 0;
+  if (tid == 0) { n_long_items = 0; n_short_partial_items = 0; }
   if (tid < 64) a.counters[tid] = 0;
   __syncthreads();
 
   // full chunks and long items are counted per thread and added once per wave: nearly every
   // sequence contributes to these two words, and same-address LDS atomics run one lane at a time
-  int nfull_mine = 0, nlong_mine = 0;
+  int nfull_mine = 0, nlong_mine = 0, nshort_partial_mine = 0;
 #pragma unroll
   for (int k = 0; k < kSeqsPerThread; ++k) {
     const int s = tid + k * kPlanThreads;
@@ -284,13 +290,18 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
       nfull_mine += nfull;
       if (tail) atomicAdd(&hist_s[(Cs - tail) / 32], 1);
       nlong_mine += (Cs > kShortTokens ? nfull : 0) + (tail > kShortTokens ? 1 : 0);
+    // short items (at most kShortTokens tokens) of sequences with several suffix chunks: they become partials
+    if (nfull + (tail > 0) >= 2)
+      nshort_partial_mine += (Cs <= kShortTokens ? nfull : 0) + ((tail > 0 && tail <= kShortTokens) ? 1 : 0);
     }
   }
   nfull_mine = wave_sum(nfull_mine);
   nlong_mine = wave_sum(nlong_mine);
+  nshort_partial_mine = wave_sum(nshort_partial_mine);
   if (lane_id() == 0) {
     if (nfull_mine) atomicAdd(&hist_s[0], nfull_mine);
     if (nlong_mine) atomicAdd(&n_long_items, nlong_mine);
+    if (nshort_partial_mine) atomicAdd(&n_short_partial_items, nshort_partial_mine);
   }
   __syncthreads();
   const int nseq_grouped = block_exclusive_scan<false>(cnt, start, a.NG, tmp);
@@ -386,6 +397,7 @@ __device__ __forceinline__ void plan_in_lds(const AttnArgs& a) {
     a.counters[MARL_CTR_NUM_SUFFIX_ITEMS] = n_suffix_items;
     a.counters[MARL_CTR_NUM_PREFIX_ITEMS] = n_prefix_items;
     a.counters[MARL_CTR_NUM_LONG_SUFFIX_ITEMS] = n_long_items;
+    a.counters[MARL_CTR_NUM_SHORT_PARTIAL_ITEMS] = n_short_partial_items;
   }
 }
 

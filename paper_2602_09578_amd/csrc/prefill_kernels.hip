@@ -223,8 +223,11 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
     region[k] = k * (kNW / 4) + (wave >> 2);
     const int s_pos = w0 + lane;
     const int slot = s_pos >> 4;
+    // swizzle key of K row tau = 16 * (region & 1) + slot: bits 0, 1, 3, 4 of tau (the 16 rows one
+    // operand read touches differ in exactly those bits, so its 16 lanes hit 16 different bank groups)
+    const int key = ((region[k] & 1) << 3) | ((slot >> 3) << 2) | (slot & 3);
     const int src = (region[k] >> 1) ? (s_pos ^ ((s_pos >> 3) & 1))
-                                     : ((slot << 4) | ((s_pos & 15) ^ (slot & 3) ^ ((slot >> 1) & 4)));
+                                     : ((slot << 4) | ((s_pos & 15) ^ key));
     src_off[k] = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)src * 16;
   }
   auto issue = [&](int p0, int p1, char* buf) {
@@ -251,7 +254,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
     for (int T = 0; T < 2; ++T)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ (i & 7)) << 4));
+        kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ i) << 4));
 #pragma unroll
     for (int qt = 0; qt < kMT; ++qt) {
       if (t0 < tile_hi[qt]) {   // wave-uniform: some row of the tile sees a token of this step
@@ -327,7 +330,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
     for (int T = 0; T < 2; ++T)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ (i & 7)) << 4));
+        kr[T][kk] = *reinterpret_cast<const u32x4*>(buf + k_rd + T * 4 * 256 + (((4 * kk + j) ^ i) << 4));
     f32x4 s0[kMT], s1[kMT];
     float m_new[kMT];
 #pragma unroll

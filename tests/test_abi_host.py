@@ -168,3 +168,62 @@ def test_prefill_argument_errors_without_gpu():
     assert at(mk(num_tokens=0), None, 0, None) == 0              # nothing to do
     wr = lambda sh, k_new: lib.marl_kv_write_prompt(ctypes.byref(sh), k_new, p, p, p, p, p, p, None, None)
     assert wr(mk(), None) == -1 and wr(mk(num_groups=0), None) == 0 and wr(mk(page_size=32), p) == -2
+    # keys are copied, and whole value pages stored, as 16-byte vectors
+    off = ctypes.c_void_p(p.value + 8)
+    wr5 = lambda k_new, k_pages, v_pages: lib.marl_kv_write_prompt(ctypes.byref(mk()), k_new, p, k_pages, v_pages,
+                                                                   p, p, p, None, None)
+    assert wr5(off, p, p) == -1 and wr5(p, off, p) == -1 and wr5(p, p, off) == -1
+
+
+def test_balancer_takes_sparse_request_ids_and_reports_status_codes():
+    """Request ids are arbitrary non-negative int32 values (a hash, say): the id map must not be
+    sized by the largest id, and no error may leave the library as an exception."""
+    bal = B.Balancer([2, 1], delta=5)
+    big = 2 ** 31 - 1
+    assert bal.submit(0, big, 3) in (0, 1)
+    assert bal.submit(1, 2 ** 30 + 12345, 2) == 2
+    assert bal.submit(0, 7, 1) in (0, 1)
+    with pytest.raises(B.MarlError) as e:
+        bal.submit(0, big, 3)                      # ids are unique
+    assert e.value.status == -1
+    for _ in range(3):
+        bal.step()
+    assert bal.request_state(big)[2] == 2          # finished in the third step (0-based step 2)
+    assert bal.request_state(7)[2] == 0
+    with pytest.raises(B.MarlError):
+        bal.request_state(8)                       # unknown id
+    assert B.load_library().marl_status_string(-5) == b"out of host memory"
+    bal.close()
+
+
+def test_binding_refuses_wrong_dtypes_and_extents():
+    """The kernels reinterpret raw bytes: torch's default int64 for an index tensor, or float32 where
+    bf16 is expected, must be an error in the binding, not a wrong result."""
+    import torch
+    logits = torch.zeros((4, 100), dtype=torch.bfloat16)
+    out = torch.zeros(4, dtype=torch.float32)
+    with pytest.raises(ValueError, match="tokens: expected dtype torch.int32"):
+        B.marl_token_logprobs(logits, torch.zeros(4, dtype=torch.int64), 1.0, out)
+    with pytest.raises(ValueError, match="logits: expected dtype torch.bfloat16"):
+        B.marl_token_logprobs(logits.float(), torch.zeros(4, dtype=torch.int32), 1.0, out)
+    with pytest.raises(ValueError, match="out: expected shape"):
+        B.marl_token_logprobs(logits, torch.zeros(4, dtype=torch.int32), 1.0, torch.zeros(5))
+    shape = good_shape()
+    ws = torch.zeros(256, dtype=torch.uint8)
+    q = torch.zeros((16, 8, 128), dtype=torch.bfloat16)
+    kv = torch.zeros((100, 2, 16, 128), dtype=torch.bfloat16)
+    vv = torch.zeros((100, 2, 128, 16), dtype=torch.bfloat16)
+    pt, st = torch.zeros((4, 16), dtype=torch.int32), torch.zeros((16, 8), dtype=torch.int32)
+    pl, sl, gos = torch.zeros(4, dtype=torch.int32), torch.zeros(16, dtype=torch.int32), torch.zeros(16, dtype=torch.int32)
+    o = torch.zeros((16, 8, 128), dtype=torch.bfloat16)
+    call = lambda **kw: B.marl_decode_attn(shape, ws, **{**dict(q=q, k_pages=kv, v_pages=vv, prefix_block_table=pt,
+                                                               suffix_block_table=st, prefix_lens=pl, suffix_lens=sl,
+                                                               group_of_seq=gos, scale=1.0, out=o), **kw})
+    with pytest.raises(ValueError, match="suffix_lens: expected dtype"):
+        call(suffix_lens=sl.long())
+    with pytest.raises(ValueError, match="v_pages: expected shape"):
+        call(v_pages=kv)                       # the key layout passed for the values
+    with pytest.raises(ValueError, match="out: expected dtype"):
+        call(out=o.float())
+    with pytest.raises(ValueError, match="device tensors required"):
+        call()                                 # everything right except that these are host tensors

@@ -44,6 +44,7 @@ def compare(shape, pl, sl, gos, Hq, Hkv):
     assert got["ctr"][B.CTR_SHORT_CURSOR] == 0
     nlong = got["ctr"][B.CTR_NUM_LONG_SUFFIX_ITEMS]
     assert nlong == want.num_long_suffix_items
+    assert got["ctr"][B.CTR_NUM_SHORT_PARTIAL_ITEMS] == want.num_short_partial_items
     assert all(it[2] - it[1] > plan_ref.SHORT_TOKENS for it in got["sitems"][:nlong].tolist())
     assert all(it[2] - it[1] <= plan_ref.SHORT_TOKENS for it in got["sitems"][nlong:].tolist())
     for items, ref_items, chunk in ((got["sitems"], want.suffix_items, want.Cs),

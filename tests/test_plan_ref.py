@@ -48,3 +48,17 @@ def test_default_chunk_rule():
     assert plan_ref.default_chunks(2048, 64, 28, 4, 256, 4) == (8192, 8192)      # 224 rows: two row blocks
     assert plan_ref.default_chunks(64, 8, 8, 2, 256, 512) == (512, 256)
     assert plan_ref.default_chunks(16, 4, 8, 2, 16, 8, 64, 96) == (64, 96)
+
+
+def test_long_and_short_item_counts_on_a_hand_worked_list():
+    """Chunks of 256 tokens; short = at most 128 tokens.  Own tokens 600 -> items 256, 256, 88 (the 88
+    is short and belongs to a sequence with several chunks); 100 -> one short item that is the whole
+    sequence; 256 -> one long item; 260 -> 256 and 4 (short, several chunks); 0 -> nothing."""
+    p = plan_ref.build_plan([10], [600, 100, 256, 260, 0], [0] * 5, 4, 2, 1, 64, suffix_chunk=256, prefix_chunk=32)
+    assert len(p.suffix_items) == 7
+    assert p.num_long_suffix_items == 4
+    assert p.num_short_partial_items == 2
+    # chunks no longer than a short item: every chunk of a sequence with several chunks counts
+    p = plan_ref.build_plan([10], [200, 64, 70], [0] * 3, 4, 2, 1, 64, suffix_chunk=64, prefix_chunk=32)
+    assert p.num_long_suffix_items == 0
+    assert p.num_short_partial_items == 4 + 0 + 2

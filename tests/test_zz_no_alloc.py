@@ -67,7 +67,8 @@ def test_static_workspace_entry_reports_flags_and_handles_empty_batches():
     # an empty batch runs no kernel of the path and reports no flag
     empty = B.make_shape(0, 0, 8, 2, 1, 0, 0, B.MARL_OUT_F32)
     flags.fill_(-1)
-    B.marl_decode_attn_static(empty, None, None, None, None, None, None, None, None, 1.0, call.out, flags)
+    no_rows = torch.empty((0, 8, 128), dtype=torch.float32, device="cuda")
+    B.marl_decode_attn_static(empty, None, None, None, None, None, None, None, None, 1.0, no_rows, flags)
     torch.cuda.synchronize()
     assert int(flags.item()) == 0
 
