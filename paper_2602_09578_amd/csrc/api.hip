@@ -443,7 +443,7 @@ int marl_kv_copy_pages(const marl_attn_shape* shape, void* k_pages, void* v_page
 // ---- log-probabilities ------------------------------------------------------------------------
 static int logprob_split(int32_t rows, int32_t vocab, int32_t* slices, int32_t* slice_len) {
   if (rows < 0 || vocab < 1) return MARL_INVALID_ARG;
-  long want = rows > 0 ? (2048 + rows - 1) / rows : 1;     // aim for >= 2048 workgroups
+  long want = rows > 0 ? (1024 + rows - 1) / rows : 1;     // aim for >= 1024 workgroups (of 1024 threads)
   long len = (vocab + want - 1) / want;
   if (len < 8192) len = 8192;                              // but keep slices worth a workgroup
   len = (len + 2047) / 2048 * 2048;

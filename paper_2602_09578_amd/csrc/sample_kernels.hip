@@ -12,6 +12,7 @@
 #include <type_traits>
 
 #include "marl_internal.h"
+#include "wave_ops.h"
 
 namespace marl {
 namespace {
@@ -57,33 +58,6 @@ __device__ __forceinline__ u32x4 load8_words(const uint16_t* x, long pos, long e
   return v;
 }
 
-// Reductions over the 64 lanes, result in every lane, inside the vector ALU: four DPP steps
-// all-reduce each row of 16 lanes (swap neighbours, swap pairs, mirror the halves of 8, mirror
-// the row), two row swaps combine the four rows.  (A shuffle-based reduction keeps six
-// lane-address registers alive and goes through the LDS crossbar six times per call, each a
-// dependent round trip.)
-template <class T, class Op>
-__device__ __forceinline__ T wave_allreduce(T v, Op op) {
-  static_assert(sizeof(T) == 4, "32-bit values");
-  auto dpp = [](T x, auto ctrl_tag) {
-    constexpr int ctrl = decltype(ctrl_tag)::value;
-    return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xf, 0xf, false));
-  };
-  v = op(v, dpp(v, std::integral_constant<int, 0xB1>{}));    // quad_perm [1, 0, 3, 2]
-  v = op(v, dpp(v, std::integral_constant<int, 0x4E>{}));    // quad_perm [2, 3, 0, 1]
-  v = op(v, dpp(v, std::integral_constant<int, 0x141>{}));   // row_half_mirror
-  v = op(v, dpp(v, std::integral_constant<int, 0x140>{}));   // row_mirror
-  // (the swap results are copied to scalars first: a bit cast applied directly to an element of
-  // the returned vector reads element 0 for both)
-  const uint32_t u = __builtin_bit_cast(uint32_t, v);
-  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const uint32_t a0 = a[0], a1 = a[1];
-  v = op(__builtin_bit_cast(T, a0), __builtin_bit_cast(T, a1));
-  const uint32_t w = __builtin_bit_cast(uint32_t, v);
-  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-  const uint32_t b0 = b[0], b1 = b[1];
-  return op(__builtin_bit_cast(T, b0), __builtin_bit_cast(T, b1));
-}
 template <class T>
 __device__ __forceinline__ T wave_allreduce_sum(T v) { return wave_allreduce(v, [](T x, T y) { return x + y; }); }
 __device__ __forceinline__ float wave_max(float v) { return wave_allreduce(v, [](float x, float y) { return fmaxf(x, y); }); }

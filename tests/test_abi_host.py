@@ -102,7 +102,7 @@ def test_logprobs_argument_errors_without_gpu():
     assert f(p, 1.0, 4, 152064, None, 0) == -1                 # sliced launch needs a workspace
     assert f(p, 1.0, 4, 152064, p, 8) == -3
     assert B.marl_logprobs_workspace_bytes(2048, 152064) == 0
-    assert B.marl_logprobs_workspace_bytes(256, 152064) == 256 * 8 * 8
+    assert B.marl_logprobs_workspace_bytes(256, 152064) == 256 * 4 * 8        # four vocabulary slices per row
     assert lib.marl_status_string(-3) == b"workspace too small"
 
 
