@@ -123,25 +123,37 @@ __global__ __launch_bounds__(64) void sample_pick_kernel(SampleArgs a) {
   const float2* part = a.partials + (size_t)row * a.num_chunks;
   const uint16_t* x = a.logits + (size_t)row * a.vocab;
   const float c = a.inv_temp_log2e;
-  // global max and total, chunk sums rescaled to the global max
+  // global max and total, chunk sums rescaled to the global max.  The few dozen chunk sums are
+  // accumulated in double precision: they decide in which chunk the uniform number falls, and a
+  // float32 running sum over the whole vocabulary would move a CDF step by up to ~1e-5.
   float M = -INFINITY;
   for (int k = lane; k < a.num_chunks; k += 64) M = fmaxf(M, part[k].x);
   M = wave_max(M);
-  float total = 0.f;
-  for (int base = 0; base < a.num_chunks; base += 64) {   // fixed order: tiles of 64 chunks
-    const int k = base + lane;
-    total += wave_sum(k < a.num_chunks ? part[k].y * ex2_diff(part[k].x, M) : 0.f);
-  }
-  const float target = a.uniforms[row] * total;
+  auto chunk_mass = [&](int k) -> double {
+    return k < a.num_chunks ? (double)(part[k].y * ex2_diff(part[k].x, M)) : 0.0;
+  };
+  auto scan_d = [&](double v) {   // inclusive scan over the wave, fixed order
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const double t = __shfl_up(v, d);
+      if (lane >= d) v += t;
+    }
+    return v;
+  };
+  double total = 0.0;
+  for (int base = 0; base < a.num_chunks; base += 64)   // fixed order: tiles of 64 chunks
+    total += __shfl(scan_d(chunk_mass(base + lane)), 63);
+  const double target = (double)a.uniforms[row] * total;
   // the chunk in which the running sum passes the target
-  float before = 0.f;
+  double before = 0.0;
+  bool take_last = false;
   int chunk = -1, last_nonzero = -1;
   for (int base = 0; base < a.num_chunks && chunk < 0; base += 64) {
     const int k = base + lane;
-    const float v = k < a.num_chunks ? part[k].y * ex2_diff(part[k].x, M) : 0.f;
-    const float cum = before + wave_inclusive_scan(v, lane);
+    const double v = chunk_mass(k);
+    const double cum = before + scan_d(v);
     const unsigned long long hit = __builtin_amdgcn_ballot_w64(k < a.num_chunks && cum > target);
-    const unsigned long long nz = __builtin_amdgcn_ballot_w64(v > 0.f);
+    const unsigned long long nz = __builtin_amdgcn_ballot_w64(v > 0.0);
     if (nz) last_nonzero = base + 63 - __builtin_clzll(nz);
     if (hit) {
       const int l = __builtin_ctzll(hit);
@@ -153,9 +165,10 @@ __global__ __launch_bounds__(64) void sample_pick_kernel(SampleArgs a) {
   }
   if (chunk < 0) {   // rounding: u * total not below the last partial sum
     chunk = max(last_nonzero, 0);
-    before = -INFINITY;   // any non-zero element of the chunk passes; the last one is taken below
+    take_last = true;   // any non-zero element of the chunk passes; the last one is taken below
   }
-  const float want = target - before;   // remaining mass to pass inside the chunk (+inf = take the last)
+  // remaining mass to pass inside the chunk (-inf: nothing passes, the last non-zero token is taken)
+  const float want = take_last ? INFINITY : (float)(target - before);
   const long cbase = (long)chunk * kChunk;
   float run = 0.f;
   int tok = -1, last_tok = -1;
@@ -207,7 +220,7 @@ __global__ __launch_bounds__(64) void sample_pick_kernel(SampleArgs a) {
       a.out_logprobs[row] = __uint_as_float(0x7fc00000u);
     } else {
       a.out_tokens[row] = tok;
-      a.out_logprobs[row] = (y_tok - (M + __builtin_amdgcn_logf(total))) * 0.69314718055994530942f;
+      a.out_logprobs[row] = (y_tok - (M + __builtin_amdgcn_logf((float)total))) * 0.69314718055994530942f;
     }
   }
 }
@@ -262,7 +275,7 @@ struct TpShared {
   int thr_key, thr_cnt;         // threshold value (key) and how many tokens have it
   double thr_above;             // mass strictly above the threshold value
   int tile, ties_before;
-  float cum_before;
+  float want_in_tile;           // nucleus mass still to pass inside the chosen tile
   int out_tok;
   float out_y;
 };
@@ -509,7 +522,10 @@ __device__ __forceinline__ void sample_top_p_body(const TopPArgs& a) {
     ties_kept = uniform_i((int)fmin(fmax(ceil(need), 1.0), (double)sh.thr_cnt));
     nucleus = sh.thr_above + (double)ties_kept * (double)thr_w;
   }
-  const float target = uniform_f((float)((double)a.uniforms[row] * nucleus));
+  // the walk over the tile sums runs in double precision (a float32 running sum over the whole
+  // vocabulary would move a CDF step by up to ~1e-5 of the nucleus mass); inside the chosen tile
+  // float32 sums start from zero again and are compared with the mass that is left to pass
+  const double target = (double)a.uniforms[row] * nucleus;
   // pass 3 compares raw logit values (every bf16 is exact in float; -0 == +0 as in the keys);
   // with no threshold every finite logit is above it
   const float thr_x = uniform_f(thr_key >= 0 ? value_of_key(thr_key) : -INFINITY);
@@ -537,15 +553,14 @@ __device__ __forceinline__ void sample_top_p_body(const TopPArgs& a) {
   });
   __syncthreads();
   if (tid == 0) {
-    float cum = 0.f;
+    double cum = 0.0, last_cum = 0.0;
     int ties = 0, tile = -1, last_tile = 0, last_ties = 0;
-    float last_cum = 0.f;
     for (int t = 0; t < ntiles && tile < 0; ++t) {
-      float m = 0.f;
+      double m = 0.0;
       int n = 0;
-      for (int w = 0; w < kTpWaves; ++w) { m += part_m[t * kTpWaves + w]; n += part_n[t * kTpWaves + w]; }
-      const float kept = m + thr_w * (float)min(n, max(0, ties_kept - ties));
-      if (kept > 0.f) { last_tile = t; last_cum = cum; last_ties = ties; }
+      for (int w = 0; w < kTpWaves; ++w) { m += (double)part_m[t * kTpWaves + w]; n += part_n[t * kTpWaves + w]; }
+      const double kept = m + (double)thr_w * (double)min(n, max(0, ties_kept - ties));
+      if (kept > 0.0) { last_tile = t; last_cum = cum; last_ties = ties; }
       if (cum + kept > target) { tile = t; break; }
       cum += kept;
       ties += n;
@@ -556,7 +571,7 @@ __device__ __forceinline__ void sample_top_p_body(const TopPArgs& a) {
       ties = last_ties;
     }
     sh.tile = tile;
-    sh.cum_before = cum;
+    sh.want_in_tile = (float)(target - cum);
     sh.ties_before = ties;
     sh.found_at = kTpThreads;
     sh.out_tok = -1;
@@ -590,8 +605,9 @@ __device__ __forceinline__ void sample_top_p_body(const TopPArgs& a) {
       w8[e] = w;
       m8 += w;
     }
-    const float before = sh.cum_before + block_excl_scan_f(m8, sh);
-    const bool pass = before + m8 > target && m8 > 0.f;
+    const float want = sh.want_in_tile;
+    const float before = block_excl_scan_f(m8, sh);
+    const bool pass = before + m8 > want && m8 > 0.f;
     if (pass) atomicMin(&sh.found_at, tid);
     // the last thread of the tile that holds a nucleus token, for the rounding fallback
     if (m8 > 0.f) atomicMax(&sh.out_tok, tid);
@@ -610,7 +626,7 @@ __device__ __forceinline__ void sample_top_p_body(const TopPArgs& a) {
         if (w8[e] > 0.f) {
           run += w8[e];
           if (fallback) e_pick = e;                               // last nucleus token of the thread
-          else if (e_pick < 0 && run > target) e_pick = e;
+          else if (e_pick < 0 && run > want) e_pick = e;
         }
       }
       if (e_pick < 0) {                                           // cannot happen: pass implies a hit

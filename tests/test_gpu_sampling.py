@@ -1,8 +1,10 @@
 """GPU parity of marl_sample_tokens.  The token is an integer decided by float32 sums on the
 GPU and float64 sums in the reference, so a drawn token is accepted when the reference CDF
-brackets the uniform within 1e-5 (what float32 accumulation over the vocabulary can move a
-step by); it must equal the reference token whenever the uniform is further than that from
-every CDF step.  Its log-probability must match the reference's for that token to 1e-3."""
+brackets the uniform within 2e-6 (the kernel adds the few dozen chunk sums in double precision;
+what is left is the float32 rounding inside a 4096-logit chunk); it must equal the reference
+token whenever the uniform is further than that from every CDF step, which at the 152064-token
+vocabulary is the case for about nine draws in ten.  Its log-probability must match the
+reference's for that token to 1e-3."""
 import numpy as np
 import pytest
 import torch
@@ -12,7 +14,7 @@ from paper_2602_09578_amd import binding as B
 from paper_2602_09578_amd import inputs as I
 
 pytestmark = pytest.mark.gpu
-CDF_TOL = 1e-5
+CDF_TOL = 2e-6
 
 
 def run(lp: I.LogprobInputs, u: np.ndarray):
@@ -58,6 +60,8 @@ def test_sampled_tokens_are_valid_and_logprobs_match(rows, vocab, T):
     exact = check(lp, u)
     if 64 <= vocab <= 8192:      # CDF steps are far apart compared with the tolerance: nearly every draw is decidable
         assert exact >= rows - 2
+    if rows >= 40:               # also at the real vocabulary most draws are decided, and decided right
+        assert exact >= 0.85 * rows, (exact, rows)
 
 
 def test_uniform_logits_and_masked_vocabulary():

@@ -1,9 +1,9 @@
 """GPU parity of marl_sample_tokens_top_p.  Two integers are decided by floating-point sums
 (float32 on the GPU, float64 in the reference): which value is the nucleus threshold, and
 which token passes the scaled uniform.  A drawn token is accepted when it is what the
-reference draws for top_p and u moved by at most 2e-5 (relative) / 1e-5 (of the nucleus mass);
-it must EQUAL the reference token whenever no nucleus boundary lies within 2e-5 of top_p and
-no CDF step within 1e-5 of u.  The log-probability must match the reference's for that token
+reference draws for top_p and u moved by at most 4e-6 (relative) / 2e-6 (of the nucleus mass);
+it must EQUAL the reference token whenever no nucleus boundary lies within 4e-6 of top_p and
+no CDF step within 2e-6 of u.  The log-probability must match the reference's for that token
 to 1e-3."""
 import numpy as np
 import pytest
@@ -14,7 +14,7 @@ from paper_2602_09578_amd import binding as B
 from paper_2602_09578_amd import inputs as I
 
 pytestmark = pytest.mark.gpu
-P_TOL, CDF_TOL = 2e-5, 1e-5
+P_TOL, CDF_TOL = 4e-6, 2e-6
 
 
 def run(logits: torch.Tensor, u: np.ndarray, T: float, top_p: float):
@@ -76,6 +76,7 @@ def test_tokens_match_the_reference(rows, vocab, T, top_p):
     if rows > 1:
         u[1] = np.nextafter(np.float32(1.0), np.float32(0.0))
     exact = check(lp.logits, u, T, top_p)
+    print("exactly decided draws:", exact, "of", rows, flush=True)
     # where the steps of the ranking's running mass and of the CDF are far apart compared with the
     # tolerances, nearly every draw is decidable (with top_p = 0.99 the boundary lies among tail
     # tokens of probability ~1e-5 and is rarely decidable)
