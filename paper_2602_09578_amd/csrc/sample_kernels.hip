@@ -234,26 +234,28 @@ __global__ __launch_bounds__(64) void sample_pick_kernel(SampleArgs a) {
 // tokens at the threshold value": the kernel finds the threshold with an exact counting
 // histogram over the values instead of sorting 150 k tokens.
 //
-// One workgroup of 1024 threads owns a row and makes these passes over it.  Rows of up to
-// kTpRegTiles * 8192 logits (163840: the vocabularies in use) are read from memory ONCE and kept
-// in registers, 16 bytes per thread and tile; longer rows are re-read from the caches / HBM for
-// every pass (16-byte loads):
+// One workgroup of 512 threads owns a row and makes these passes over it.  Rows of up to
+// kTpRegTiles * 4096 logits (163840: the vocabularies in use) are read from memory ONCE and kept
+// in registers, 16 bytes per thread and tile (160 of a thread's 229 registers: with 1024 threads,
+// i.e. 128 registers per thread, the compiler kept 6 of 20 tiles in scratch memory, 0.24 GB of
+// writes per call on 2048 x 152064 logits; the time is the same either way); longer rows are
+// re-read from the caches / HBM for every pass (16-byte loads):
 //   1. maximum value and Z = sum 2^(y - M)  (running (max, sum) per thread, fixed-order merge);
 //   2. count histogram in LDS over the 32768 values just below the maximum (order-preserving
 //      16-bit key of the bf16 pattern; integer LDS atomics, so the result does not depend on
 //      the order); a scan of value masses count * 2^(y(value) - M) from the top finds where the
 //      cumulative mass reaches top_p * Z.  If that lies below the window (flat rows with top_p
 //      near 1), the window moves down and the pass repeats (all 65536 values fit 2 windows);
-//   3. per tile of 8192 tokens the nucleus mass and the number of threshold-value tokens; a
+//   3. per tile of 4096 tokens the nucleus mass and the number of threshold-value tokens; a
 //      sequential walk over the tile sums finds the tile in which the scaled uniform is
 //      passed, a workgroup scan inside that tile finds the token.
 // ---------------------------------------------------------------------------------------
-constexpr int kTpThreads = 1024;
+constexpr int kTpThreads = 512;
 constexpr int kTpWaves = kTpThreads / 64;
 constexpr int kWin = 32768;                  // histogram window, in values (keys)
 constexpr int kTile = kTpThreads * 8;        // tokens per tile of pass 3
 constexpr int kLowestKey = 0x0080;           // key of the most negative finite bf16; below: -inf, NaN
-constexpr int kTpRegTiles = 20;              // tiles of a row that the register-resident variant holds
+constexpr int kTpRegTiles = 40;              // tiles of a row that the register-resident variant holds
 constexpr int kScanStep = 4;                 // scan positions per thread and round of the threshold search
 
 __device__ __forceinline__ int key_of(uint32_t bits) {   // larger value <=> larger key; -0 counts as +0
