@@ -28,10 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes one suffix_kernel launch moves on this workload, from hardware counters
 # (profiles/decode_step_qwen7b_hbm_counters.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
-# factors a copy kernel of known size gives).  Valid only for the kernel source and flags it was taken
+# factors that the one-launch copy of the weight_pack leg, a copy kernel of known size in the same
+# run, gives).  Valid only for the kernel source and flags it was taken
 # with: reported as null when either has changed since.
-SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5556.9e6 + 14.1e6,
-                  "kernel_sources_sha256": "e77282e3c056186aa3d70d62064b0be2a6b236159a154a4c4827feb69caca86d"}
+SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5556.8e6 + 14.1e6,
+                  "kernel_sources_sha256": "33d9417a98f3737c6bbe77badb0049d0495fbe94fe27e077582ecfd1fea8f1b2"}
 SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 
