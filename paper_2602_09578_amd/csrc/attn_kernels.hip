@@ -517,46 +517,64 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
 
   const int nsteps = (tok_end - tok_begin + kBlockTok - 1) / kBlockTok;
   const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
-  const char* dummy = reinterpret_cast<const char*>(a.q);   // any valid 16 bytes
 
-  // Page ids of step n (wave-uniform scalar loads); steps past the end yield -1.
-  auto load_ids = [&](int n, int& p0, int& p1) {
-    p0 = -1;
-    p1 = -1;
-    if (n < nsteps) {
-      const int t = tok_begin + n * kBlockTok;
-      p0 = ld_uniform(table_row + (t >> 4));
-      p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
-      if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
-      if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
-    }
+  // The loop below runs two waves per SIMD and a wave issues an instruction every four to five
+  // cycles whatever it is, so what a step costs is its instruction count: page ids and addresses
+  // are wave-uniform (scalar registers, a handful of scalar instructions per step) and every lane
+  // adds one 32-bit offset that never changes (the loads take a scalar base and a vector offset).
+  //
+  // Page ids of step n: two scalar loads, unconditional (a step past the end repeats the last page,
+  // and so does the second page of a step that has only one).  They are issued at the top of an
+  // iteration and taken after its first wait for LDS data, which waits for scalar loads as well
+  // (one counter, and scalar loads return out of order); fetched and checked in one place they
+  // would cost two scalar-memory latencies per step, one after the other.
+  const int first_page = tok_begin >> 4;
+  const int last_page = max(first_page, (tok_end - 1) >> 4);
+  uint32_t id_max = 0;   // largest id seen (as unsigned): checked against the pool once, after the loop
+  auto fetch_ids = [&](int n, int& r0, int& r1) {
+    r0 = ld_uniform(table_row + min(first_page + 2 * n, last_page));
+    r1 = ld_uniform(table_row + min(first_page + 2 * n + 1, last_page));
+  };
+  // the ids as the loads use them: page 0 (bytes nobody uses, from cache) for a step past the end
+  // and for an id outside the pool
+  auto take_ids = [&](int n, int r0, int r1, int& p0, int& p1) {
+    id_max = max(id_max, max((uint32_t)r0, (uint32_t)r1));
+    const uint32_t limit = n < nsteps ? (uint32_t)a.num_pages : 0u;
+    p0 = (uint32_t)r0 < limit ? r0 : 0;
+    p1 = (uint32_t)r1 < limit ? r1 : 0;
+    // (an empty statement the compiler may not move: without it the loads and the check sink to
+    // the end of the iteration, in front of the next use, and are waited for there)
+    asm volatile("" : "+s"(p0), "+s"(p1));
   };
   // A step is 1024 16-byte vectors: K of page 0, K of page 1, V of page 0, V of page 1 (256
   // each, contiguous in memory).  Thread tid fetches vectors tid + k * (threads), k < kLoads.
   // Of a page's 256 vectors, vector w is slot w/16, chunk w%16 of K, or 16-byte unit w of V.
-  const char* src_base[kLoads];
+  // Which of the four regions a load belongs to is the same for a whole wave.
+  static_assert(NW % 4 == 0, "a wave's 64 vectors must lie in one 256-vector region");
+  const int w = tid & 255;
+  const uint32_t lane_off = (uint32_t)kvh * (kPage * kD * 2) + (uint32_t)w * 16;
+  auto region_of = [&](int k) { return NW == 4 ? k : k * (NW / 4) + (wave >> 2); };   // wave-uniform
   int lds_off[kLoads];
-  bool second_page[kLoads];
 #pragma unroll
   for (int k = 0; k < kLoads; ++k) {
-    const int v = tid + k * NW * 64;
-    const int region = v >> 8, w = v & 255;
-    second_page[k] = region & 1;
+    const int region = region_of(k);
     const bool is_v = region >> 1;
-    src_base[k] = reinterpret_cast<const char*>(is_v ? a.v_pages : a.k_pages) + (size_t)kvh * (kPage * kD * 2) + w * 16;
     // K rows of page 1 are tau = 16 + slot; swizzle key of row tau: bits 0, 1, 3, 4 of tau
     const int slot = w >> 4;
     const int key = ((region & 1) << 3) | ((slot >> 3) << 2) | (slot & 3);
     lds_off[k] = is_v ? 2 * kBlockTok * kD + (region & 1) * 4096 + ((w ^ ((w >> 3) & 1)) << 4)
                       : ((region & 1) * 16 + slot) * 256 + (((w & 15) ^ key) << 4);
   }
-  // The loads are unconditional (a step past the end re-reads 16 valid bytes that are never
-  // used) so that every wait in the loop knows exactly how many younger loads are in flight.
+  // The loads are unconditional so that every wait in the loop knows exactly how many younger loads
+  // are in flight.
   auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
-    const bool ok = p0 >= 0;
 #pragma unroll
-    for (int k = 0; k < kLoads; ++k)
-      st[k] = ld_stream(ok ? src_base[k] + (size_t)(second_page[k] ? p1 : p0) * page_bytes : dummy);
+    for (int k = 0; k < kLoads; ++k) {
+      const int region = region_of(k);
+      const char* base = reinterpret_cast<const char*>((region >> 1) ? a.v_pages : a.k_pages) +
+                         (size_t)(uint32_t)((region & 1) ? p1 : p0) * page_bytes;   // scalar
+      st[k] = ld_stream(base + lane_off);
+    }
   };
   auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
 #pragma unroll
@@ -566,10 +584,13 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
   const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
 
+  int r0, r1;   // ids in flight: those of the step that the next iteration requests
+  int p0, p1;   // the ids the next request uses
   auto compute = [&](int n, const char* buf) {
     const int t0 = tok_begin + n * kBlockTok;
     const bool ragged = t0 + kBlockTok > tok_end;   // wave-uniform; only the chunk's last step
     u32x4 pb[MTW];
+    if (nt == 0) take_ids(n + 4, r0, r1, p0, p1);   // (a wave without tiles only moves data)
     {
       u32x4 kr[2][4];
 #pragma unroll
@@ -587,6 +608,7 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
             s0 = mfma_16x16x32(kr[0][kk], qreg[qt][kk], s0);
             s1 = mfma_16x16x32(kr[1][kk], qreg[qt][kk], s1);
           }
+          if (qt == 0) take_ids(n + 4, r0, r1, p0, p1);   // (the K reads have been waited for)
           if (ragged) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -644,37 +666,41 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   // the loads of steps n+1, n+2 and n+3 are in flight (48 KB per workgroup); step n+1 moves
   // from its registers to buffer (n+1)%3 at the end of the iteration, one barrier per step.
   u32x4 st0[kLoads], st1[kLoads], st2[kLoads];
-  int p0, p1;
-  load_ids(0, p0, p1);
+  fetch_ids(0, r0, r1);
+  take_ids(0, r0, r1, p0, p1);
   issue(p0, p1, st0);
-  load_ids(1, p0, p1);
+  fetch_ids(1, r0, r1);
+  take_ids(1, r0, r1, p0, p1);
   issue(p0, p1, st1);
-  load_ids(2, p0, p1);
+  fetch_ids(2, r0, r1);
+  take_ids(2, r0, r1, p0, p1);
   issue(p0, p1, st2);
-  load_ids(3, p0, p1);
+  fetch_ids(3, r0, r1);
+  take_ids(3, r0, r1, p0, p1);
   stage_to_lds(st0, lds.buf[0]);
   __syncthreads();
   for (int n = 0; n < nsteps; n += 3) {
     issue(p0, p1, st0);          // step n+3
-    load_ids(n + 4, p0, p1);
-    compute(n, lds.buf[0]);
+    fetch_ids(n + 4, r0, r1);
+    compute(n, lds.buf[0]);      // (takes the ids of step n+4)
     stage_to_lds(st1, lds.buf[1]);
     __syncthreads();
     if (n + 1 < nsteps) {
       issue(p0, p1, st1);        // step n+4
-      load_ids(n + 5, p0, p1);
+      fetch_ids(n + 5, r0, r1);
       compute(n + 1, lds.buf[1]);
       stage_to_lds(st2, lds.buf[2]);
       __syncthreads();
     }
     if (n + 2 < nsteps) {
       issue(p0, p1, st2);        // step n+5
-      load_ids(n + 6, p0, p1);
+      fetch_ids(n + 6, r0, r1);
       compute(n + 2, lds.buf[2]);
       stage_to_lds(st0, lds.buf[0]);
       __syncthreads();
     }
   }
+  if (id_max >= (uint32_t)a.num_pages) bad_page = 1;
   // a workgroup-wide barrier has been passed since the last LDS read: the next item may
   // overwrite the buffers
 
@@ -724,17 +750,28 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
   const int nsteps = (tok_end - tok_begin + kBlockTok - 1) / kBlockTok;
   const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
 
-  // Page ids of step n (wave-uniform scalar loads); -1 for a step past the end.
-  auto load_ids = [&](int n, int& p0, int& p1) {
-    p0 = -1;
-    p1 = -1;
-    if (n < nsteps) {
-      const int t = tok_begin + n * kBlockTok;
-      p0 = ld_uniform(table_row + (t >> 4));
-      p1 = (t + kPage < tok_end) ? ld_uniform(table_row + (t >> 4) + 1) : p0;
-      if ((unsigned)p0 >= (unsigned)a.num_pages) { p0 = 0; bad_page = 1; }
-      if ((unsigned)p1 >= (unsigned)a.num_pages) { p1 = 0; bad_page = 1; }
+  // Page ids, as in the plain item; here a wave's loads of a step all belong to one page (the
+  // waves of the lower half of the workgroup fetch the step's first page, the others its second),
+  // so a wave needs one id per step.
+  const int first_page = tok_begin >> 4;
+  const int last_page = max(first_page, (tok_end - 1) >> 4);
+  const int my_half = NW == 8 ? (wave >> 2) : 0;
+  uint32_t id_max = 0;
+  auto fetch_ids = [&](int n, int& r0, int& r1) {
+    if constexpr (NW == 8) {
+      r0 = ld_uniform(table_row + min(first_page + 2 * n + my_half, last_page));
+      r1 = r0;
+    } else {
+      r0 = ld_uniform(table_row + min(first_page + 2 * n, last_page));
+      r1 = ld_uniform(table_row + min(first_page + 2 * n + 1, last_page));
     }
+  };
+  auto take_ids = [&](int n, int r0, int r1, int& p0, int& p1) {
+    id_max = max(id_max, max((uint32_t)r0, (uint32_t)r1));
+    const uint32_t limit = n < nsteps ? (uint32_t)a.num_pages : 0u;
+    p0 = (uint32_t)r0 < limit ? r0 : 0;
+    p1 = (uint32_t)r1 < limit ? r1 : 0;
+    asm volatile("" : "+s"(p0), "+s"(p1));   // (keeps the loads and the check where they are written)
   };
   // A step is 1024 16-byte vectors: K of page 0, K of page 1, V of page 0, V of page 1 (256 each,
   // contiguous in memory).  Thread tid fetches vectors tid + k * threads, k < kLoads.  Of a page's
@@ -751,16 +788,17 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
   const int sl = w >> 4;
   const int lds_k = sl * 256 + (((w & 15) ^ (((sl >> 3) << 2) | (sl & 3))) << 4);   // page 0; page 1: + 4096, chunk ^ 8
   const int lds_v = 2 * kBlockTok * kD + ((w ^ ((w >> 3) & 1)) << 4);              // page 0; page 1: + 4096
-  auto region_of = [&](int k) { return k * (NW / 4) + (wave >> 2); };               // wave-uniform
+  auto region_of = [&](int k) { return NW == 4 ? k : k * (NW / 4) + (wave >> 2); };   // wave-uniform
+  // (unconditional loads: a step past the end reads page 0, bytes nobody uses, from cache, so that
+  // every wait knows how many loads are in flight)
   auto issue = [&](int p0, int p1, u32x4 (&st)[kLoads]) {
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
       const int region = region_of(k);
-      // a step past the end re-reads the start of the key array (bytes nobody uses, from cache), so
-      // that the loads stay unconditional and every wait knows how many are in flight
-      const char* base = reinterpret_cast<const char*>((region >> 1) && p0 >= 0 ? a.v_pages : a.k_pages) +
-                         (p0 >= 0 ? (size_t)((region & 1) ? p1 : p0) * page_bytes : (size_t)0);
-      st[k] = ld_stream(base + (p0 >= 0 ? lane_off : 0u));
+      const int pid = NW == 8 ? p0 : ((region & 1) ? p1 : p0);   // (with 8 waves p0 is this wave's page)
+      const char* base = reinterpret_cast<const char*>((region >> 1) ? a.v_pages : a.k_pages) +
+                         (size_t)(uint32_t)pid * page_bytes;   // scalar
+      st[k] = ld_stream(base + lane_off);
     }
   };
   auto stage_to_lds = [&](const u32x4 (&st)[kLoads], char* buf) {
@@ -774,13 +812,15 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
   // the first three steps are requested before anything else of the item: the chain of dependent
   // loads that leads to the query rows then runs while they are in flight
   u32x4 st[3][kLoads];   // steps in flight: three register stages
-  int p0, p1;
+  int p0, p1, r0, r1;
 #pragma unroll
   for (int s0 = 0; s0 < 3; ++s0) {
-    load_ids(s0, p0, p1);
+    fetch_ids(s0, r0, r1);
+    take_ids(s0, r0, r1, p0, p1);
     issue(p0, p1, st[s0]);
   }
-  load_ids(3, p0, p1);
+  fetch_ids(3, r0, r1);
+  take_ids(3, r0, r1, p0, p1);
 
   const int gstart = a.group_start[g];
   const int nrows = a.group_count[g] * a.R;
@@ -938,7 +978,8 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
       const char* bufr = lds.buf[PH];
       char* bufw = lds.buf[(PH + 1) % 3];
       issue(p0, p1, st[PH]);
-      load_ids(n + 4, p0, p1);
+      fetch_ids(n + 4, r0, r1);
+      if constexpr (NTraw == 0) take_ids(n + 4, r0, r1, p0, p1);
       if constexpr (NTraw > 0) {
         f32x4 s[NT][2];
         if constexpr (!kFirst) {
@@ -957,6 +998,7 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
         scores_half(0, xa, s);
         __builtin_amdgcn_sched_barrier(0);
         scores_half(1, xb, s);
+        take_ids(n + 4, r0, r1, p0, p1);   // (all of K has been waited for, and the scalar loads with it)
         __builtin_amdgcn_sched_barrier(0);
         read_v_half(bufr, 0, xa);
         read_v_half(bufr, 1, xb);
@@ -1011,6 +1053,7 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
   if (nt == MTW) run(std::integral_constant<int, MTW>{});
   else if (MTW == 2 && nt == 1) run(std::integral_constant<int, 1>{});
   else run(std::integral_constant<int, 0>{});
+  if (id_max >= (uint32_t)a.num_pages) bad_page = 1;
 
 #pragma unroll
   for (int qt = 0; qt < MTW; ++qt) {
