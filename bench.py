@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # run, gives).  Valid only for the kernel source and flags it was taken
 # with: reported as null when either has changed since.
 SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5556.8e6 + 14.1e6,
-                  "kernel_sources_sha256": "33d9417a98f3737c6bbe77badb0049d0495fbe94fe27e077582ecfd1fea8f1b2"}
+                  "kernel_sources_sha256": "00b0d9819952cc9dec50d70594f81d2ce6b5c455fefa6b3dd835ad0983315e2d"}
 SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 
