@@ -1,5 +1,6 @@
 """GPU parity of marl_decode_attn against the float64 checker, element by element, through
 the C ABI.  Tolerance: max |delta| <= 4e-3."""
+import dataclasses
 import math
 
 import numpy as np
@@ -197,7 +198,8 @@ def _full_size_every_row(name):
     """Full-size workload in the launch configuration the benchmark uses (default chunks, bf16
     output, inputs generated in HBM); the checker recomputes EVERY sequence on the host copy of
     the same bytes, and every output element is compared."""
-    w = I.WORKLOADS[name]
+    w = I.WORKLOADS[name] if isinstance(name, str) else name
+    name = w.name
     dev = I.build_attn_inputs(w, device="cuda")
     call = B.prepare_attn(dev, B.MARL_OUT_BF16)
     B.run_attn(dev, call)
@@ -224,3 +226,13 @@ def _full_size_every_row(name):
 def test_full_size_every_row(name):
     print("case: full size", name, flush=True)
     _full_size_every_row(name)
+
+
+def test_full_size_sixteen_samples_per_prompt():
+    """The bench workload's shape with 16 samples per prompt instead of 8 (the paper runs a
+    parallelism of 4 x 16, Section 8.1): 112 query rows per group and KV head, which is the 4-wave
+    prefix kernel with two row tiles per wave at full size.  Every row is compared."""
+    print("case: full size, 16 samples per prompt", flush=True)
+    w = I.WORKLOADS["qwen7b"]
+    agents = tuple(I.Agent(a.prompts // 2, 16, a.prompt_len, a.gen_len) for a in w.agents)
+    _full_size_every_row(dataclasses.replace(w, name="qwen7b/G16", agents=agents))
