@@ -321,9 +321,10 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
 
   // A step that every row of the wave's tiles sees in full (no causal edge, not ragged): the
   // same arithmetic as compute_edge without masks, tile tests and per-tile branches: all score
-  // products, the row maxima, ONE test whether any row's maximum moved (rare after the first
-  // steps; the accumulators are rescaled in that branch only), then per tile the exponentials
+  // products, the row maxima, ONE test whether any row's reference maximum has to move (rare after
+  // the first steps; the accumulators are rescaled in that branch only), then per tile the exponentials
   // and that tile's output products.  About 150 vector-ALU instructions per step instead of 250.
+  constexpr float kPfRescaleSlack = 8.0f;   // log2 units
   auto compute_full = [&](int, const char* buf) {
     u32x4 kr[2][4];
 #pragma unroll
@@ -348,9 +349,13 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
     for (int qt = 0; qt < kMT; ++qt) {
       float mx = fmaxf(fmaxf(fmaxf(s0[qt][0], s0[qt][1]), fmaxf(s0[qt][2], s0[qt][3])),
                        fmaxf(fmaxf(s1[qt][0], s1[qt][1]), fmaxf(s1[qt][2], s1[qt][3])));
-      mx = rows_allreduce_max(mx);
-      m_new[qt] = fmaxf(m_run[qt], mx * sc);
-      moved |= m_new[qt] > m_run[qt];
+      mx = rows_allreduce_max(mx) * sc;
+      // the reference maximum of a row moves only when the row's maximum exceeds it by more than
+      // 2^kPfRescaleSlack (weights then stay below that), so the branch below is rare: with an exact
+      // running maximum one of a wave's 48 rows sets a new record in most steps of a long prompt
+      const bool row_moved = mx > m_run[qt] + kPfRescaleSlack;
+      m_new[qt] = row_moved ? mx : m_run[qt];
+      moved |= row_moved;
     }
     if (__builtin_amdgcn_ballot_w64(moved) != 0) {   // wave-uniform
 #pragma unroll
