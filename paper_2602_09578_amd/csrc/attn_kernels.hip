@@ -945,15 +945,17 @@ __device__ __forceinline__ void prefix_item_pipelined(const AttnArgs& a, const i
 #pragma unroll
       for (int qt = 0; qt < NT; ++qt) {
         const f32x4 s0 = s[qt][0], s1 = s[qt][1];
-        const float m8 = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
-                               fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-        mx[qt] = rows_allreduce_max(m8) * sc;
+        mx[qt] = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                       fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3]))) * sc;   // this lane's 8 tokens
         moved |= mx[qt] > m_run[qt] + kRescaleSlack;
       }
+      // (the rows' maxima, a reduction over the four lanes of a row, are needed only when some lane
+      // has seen a score that far above its row's reference)
       rescale_pending = __builtin_amdgcn_ballot_w64(moved) != 0;   // wave-uniform; rare after a chunk's first step
       if (rescale_pending) {
 #pragma unroll
         for (int qt = 0; qt < NT; ++qt) {
+          mx[qt] = rows_allreduce_max(mx[qt]);
           const float m_new = mx[qt] > m_run[qt] + kRescaleSlack ? mx[qt] : m_run[qt];
           alpha_pending[qt] = __builtin_amdgcn_exp2f(m_run[qt] - m_new);   // 1 where the row did not move
           m_run[qt] = m_new;

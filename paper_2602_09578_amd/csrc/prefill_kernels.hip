@@ -344,23 +344,26 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
         s1[qt] = mfma_16x16x32(kr[1][kk], qreg[qt][kk], s1[qt]);
       }
     }
+    // The reference maximum of a row moves only when the row's maximum exceeds it by more than
+    // 2^kPfRescaleSlack (weights then stay below that).  With an exact running maximum one of a
+    // wave's 48 rows sets a new record in most steps of a long prompt; with the slack the test below
+    // fails in nearly every step after the first few, and then neither the maxima of the rows (a
+    // reduction over four lanes each) nor new references nor rescaled accumulators are needed.
     bool moved = false;
+    float mx[kMT];
 #pragma unroll
     for (int qt = 0; qt < kMT; ++qt) {
-      float mx = fmaxf(fmaxf(fmaxf(s0[qt][0], s0[qt][1]), fmaxf(s0[qt][2], s0[qt][3])),
-                       fmaxf(fmaxf(s1[qt][0], s1[qt][1]), fmaxf(s1[qt][2], s1[qt][3])));
-      mx = rows_allreduce_max(mx) * sc;
-      // the reference maximum of a row moves only when the row's maximum exceeds it by more than
-      // 2^kPfRescaleSlack (weights then stay below that), so the branch below is rare: with an exact
-      // running maximum one of a wave's 48 rows sets a new record in most steps of a long prompt
-      const bool row_moved = mx > m_run[qt] + kPfRescaleSlack;
-      m_new[qt] = row_moved ? mx : m_run[qt];
-      moved |= row_moved;
+      mx[qt] = fmaxf(fmaxf(fmaxf(s0[qt][0], s0[qt][1]), fmaxf(s0[qt][2], s0[qt][3])),
+                     fmaxf(fmaxf(s1[qt][0], s1[qt][1]), fmaxf(s1[qt][2], s1[qt][3]))) * sc;   // this lane's 8 tokens
+      m_new[qt] = m_run[qt];
+      moved |= mx[qt] > m_run[qt] + kPfRescaleSlack;
     }
     if (__builtin_amdgcn_ballot_w64(moved) != 0) {   // wave-uniform
 #pragma unroll
       for (int qt = 0; qt < kMT; ++qt) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new[qt]);
+        const float row_mx = rows_allreduce_max(mx[qt]);
+        if (row_mx > m_run[qt] + kPfRescaleSlack) m_new[qt] = row_mx;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new[qt]);   // 1 where the row did not move
         l_run[qt] *= alpha;
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) acc[qt][ct] *= alpha;
