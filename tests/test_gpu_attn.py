@@ -148,6 +148,17 @@ def test_peaked_scores():
     check_attn(inp, B.MARL_OUT_F32, tol=4 * 2.0 ** -8, suffix_chunk_tokens=256, prefix_chunk_tokens=256)
 
 
+def test_peaked_scores_in_a_big_group():
+    """The same with a group of 21 samples (147 query rows: the 8-wave prefix kernel, whose reference
+    maximum of a row moves only when a score exceeds it by more than 2^8: with scale 1 that happens
+    in many steps, and in most of them for some rows of a wave only)."""
+    print("case: peaked scores, big group", flush=True)
+    rng = np.random.default_rng(77)
+    inp = custom_inputs([900], rng.integers(1, 40, 21), [0] * 21, 28, 4, seed=14, scale=1.0)
+    check_attn(inp, B.MARL_OUT_F32, tol=4 * 2.0 ** -8)
+    check_attn(inp, B.MARL_OUT_F32, tol=4 * 2.0 ** -8, prefix_chunk_tokens=128)
+
+
 def test_reruns_and_page_permutations_are_bit_identical():
     print("case: determinism", flush=True)
     w = I.WORKLOADS["qwen7b"].scaled(32, 8)
@@ -192,6 +203,25 @@ def test_bad_device_contents_are_clamped_and_flagged():
     got, _ = gpu_attn(bad, B.MARL_OUT_F32,
                       expect_flags=B.FLAG_BAD_GROUP | B.FLAG_LEN_CLAMPED | B.FLAG_BAD_PAGE)
     assert np.isfinite(got).all()
+
+
+@pytest.mark.parametrize("samples", [3, 21])
+def test_bad_prefix_page_ids_are_flagged(samples):
+    """A prefix block-table entry outside the pool (4-wave and 8-wave prefix kernels): the flag is
+    raised, nothing outside the buffers is read, outputs stay finite, and a group whose table is
+    intact is computed as if nothing had happened."""
+    print("case: bad prefix page ids", samples, flush=True)
+    rng = np.random.default_rng(samples)
+    gos = [0] * samples + [1] * samples
+    inp = custom_inputs([200, 150], rng.integers(1, 50, 2 * samples), gos, 28, 4, seed=15, poison=False)
+    good, _ = gpu_attn(inp, B.MARL_OUT_F32)
+    bad = I.AttnInputs(**{**inp.__dict__})
+    bad.prefix_block_table = inp.prefix_block_table.clone()
+    bad.prefix_block_table[0, 3] = 10 ** 8
+    bad.prefix_block_table[0, 7] = -5
+    got, _ = gpu_attn(bad, B.MARL_OUT_F32, expect_flags=B.FLAG_BAD_PAGE)
+    assert np.isfinite(got).all()
+    assert np.array_equal(got[samples:], good[samples:])   # the second group does not touch the bad entries
 
 
 def _full_size_every_row(name):
