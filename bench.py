@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # run, gives).  Valid only for the kernel source and flags it was taken
 # with: reported as null when either has changed since.
 SUFFIX_TRAFFIC = {"workload": "qwen7b", "bytes": 5556.8e6 + 14.1e6,
-                  "kernel_sources_sha256": "53d330fb93fd106a3538988aad8604b9ec5120992ebdb17d0513e9cb921384f5"}
+                  "kernel_sources_sha256": "1911bcbbe2344da1a3d4c8ea5234d8c7c91938043a3d9f26a3d6da4ede0b65c2"}
 SUFFIX_SOURCES = ("attn_kernels.hip", "wave_ops.h")
 
 

@@ -518,10 +518,10 @@ __device__ __forceinline__ void prefix_item(const AttnArgs& a, const int4 it, co
   const int nsteps = (tok_end - tok_begin + kBlockTok - 1) / kBlockTok;
   const size_t page_bytes = (size_t)a.Hkv * (kPage * kD * 2);
 
-  // The loop below runs two waves per SIMD and a wave issues an instruction every four to five
-  // cycles whatever it is, so what a step costs is its instruction count: page ids and addresses
-  // are wave-uniform (scalar registers, a handful of scalar instructions per step) and every lane
-  // adds one 32-bit offset that never changes (the loads take a scalar base and a vector offset).
+  // Page ids and page addresses are wave-uniform (scalar registers, a handful of scalar instructions
+  // per step) and every lane adds one 32-bit offset that never changes: with two waves per SIMD the
+  // instruction count of a step is a cost of its own (measured on the 8-wave shape, whose loop it
+  // bounds).
   //
   // Page ids of step n: two scalar loads, unconditional (a step past the end repeats the last page,
   // and so does the second page of a step that has only one).  They are issued at the top of an
