@@ -245,6 +245,7 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   const int k_rd = (8 * (i >> 2) + (i & 3)) * 256;
   const int v_rd = 2 * kBlockTok * kD + (j >> 1) * 4096;
 
+  constexpr float kPfRescaleSlack = 8.0f;   // log2 units
   auto compute_edge = [&](int n, const char* buf) {
     const int t0 = n * kBlockTok;
     const bool ragged = t0 + kBlockTok > tok_end;   // workgroup-uniform; only the last step
@@ -274,9 +275,10 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
         float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                          fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
         mx = rows_allreduce_max(mx);
-        // every row sees token 0, so after step 0 the running max is finite and a fully masked
-        // row of a later step gives alpha = 1, p = 0
-        const float m_new = fmaxf(m_run[qt], mx * sc);
+        // every row sees token 0, so after step 0 the reference maximum is finite and a fully masked
+        // row of a later step gives alpha = 1, p = 0; the reference moves only when the row's maximum
+        // exceeds it by more than 2^kPfRescaleSlack (as in the loop before the edge)
+        const float m_new = mx * sc > m_run[qt] + kPfRescaleSlack ? mx * sc : m_run[qt];
         const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
         float p[8];
 #pragma unroll
@@ -324,7 +326,6 @@ __device__ __forceinline__ void prefill_item(const PrefillArgs& a, const int g, 
   // products, the row maxima, ONE test whether any row's reference maximum has to move (rare after
   // the first steps; the accumulators are rescaled in that branch only), then per tile the exponentials
   // and that tile's output products.  About 150 vector-ALU instructions per step instead of 250.
-  constexpr float kPfRescaleSlack = 8.0f;   // log2 units
   auto compute_full = [&](int, const char* buf) {
     u32x4 kr[2][4];
 #pragma unroll
