@@ -227,3 +227,14 @@ def test_binding_refuses_wrong_dtypes_and_extents():
         call(out=o.float())
     with pytest.raises(ValueError, match="device tensors required"):
         call()                                 # everything right except that these are host tensors
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asked for more it says so and exits without touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
